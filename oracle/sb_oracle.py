@@ -1,0 +1,112 @@
+"""ctypes front end of the CPU float64 oracle (oracle/sb_oracle.c).
+
+TEST INFRASTRUCTURE: only tests/, the smoke check and the benchmark's
+cpu_baseline leg import this.  Nothing here touches the GPU library and the
+GPU library never touches this.
+
+All arrays are numpy float64, layout [B, H, T, d] (or [T, d] for one head).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sb_oracle.c")
+_LIB = os.path.join(_HERE, "libsb_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, OpenMP).  Returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+               "-ffp-contract=off", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ci = ctypes.c_int
+        lib.sb_oracle_num_threads.restype = ci
+        lib.sb_oracle_weights.argtypes = [dp, dp, ci, ci, dp, dp, dp]
+        lib.sb_oracle_weights.restype = ci
+        lib.sb_oracle_fwd.argtypes = [dp, dp, dp, dp, dp, ci, ci, ci, ci, ci, ci]
+        lib.sb_oracle_fwd.restype = ci
+        lib.sb_oracle_bwd.argtypes = [dp, dp, dp, dp, dp, dp, dp, ci, ci, ci, ci]
+        lib.sb_oracle_bwd.restype = ci
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double)) if a is not None else None
+
+
+def _as4(x):
+    x = np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+    if x.ndim == 2:
+        x = x[None, None]
+    elif x.ndim == 3:
+        x = x[None]
+    assert x.ndim == 4, "expected [T,d], [H,T,d] or [B,H,T,d]"
+    return x
+
+
+def num_threads() -> int:
+    return int(_load().sb_oracle_num_threads())
+
+
+def weights(q, k):
+    """One head, q,k [T,d] -> (A, beta, rem): A[j,i] is the paper's A[i,j]
+    (query row j, key column i), zero for i >= j; rem[j] = prod_{k<j}(1-beta)."""
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    k = np.ascontiguousarray(k, dtype=np.float64)
+    T, d = q.shape
+    A = np.empty((T, T))
+    beta = np.empty((T, T))
+    rem = np.empty(T)
+    rc = _load().sb_oracle_weights(_p(q), _p(k), T, d, _p(A), _p(beta), _p(rem))
+    if rc != 0:
+        raise RuntimeError(f"sb_oracle_weights failed: {rc}")
+    return A, beta, rem
+
+
+def fwd(q, k, v, rows=None):
+    """Forward.  Returns (o, rem) with the input's leading shape; with
+    rows=(r0, r1) only query rows r0 <= j < r1 are computed and returned."""
+    shape = np.asarray(q).shape
+    q4, k4, v4 = _as4(q), _as4(k), _as4(v)
+    B, H, T, d = q4.shape
+    r0, r1 = (0, T) if rows is None else rows
+    o = np.zeros((B, H, T, d))
+    rem = np.ones((B, H, T))
+    rc = _load().sb_oracle_fwd(_p(q4), _p(k4), _p(v4), _p(o), _p(rem), B, H, T, d, r0, r1)
+    if rc != 0:
+        raise RuntimeError(f"sb_oracle_fwd failed: {rc}")
+    o = o[:, :, r0:r1].reshape(shape[:-2] + (r1 - r0, d))
+    rem = rem[:, :, r0:r1].reshape(shape[:-2] + (r1 - r0,))
+    return o, rem
+
+
+def bwd(q, k, v, dout):
+    """Backward for upstream gradient dout = dL/do.  Returns (dq, dk, dv)."""
+    shape = np.asarray(q).shape
+    q4, k4, v4, g4 = _as4(q), _as4(k), _as4(v), _as4(dout)
+    B, H, T, d = q4.shape
+    dq = np.empty((B, H, T, d))
+    dk = np.empty((B, H, T, d))
+    dv = np.empty((B, H, T, d))
+    rc = _load().sb_oracle_bwd(_p(q4), _p(k4), _p(v4), _p(g4), _p(dq), _p(dk), _p(dv), B, H, T, d)
+    if rc != 0:
+        raise RuntimeError(f"sb_oracle_bwd failed: {rc}")
+    return dq.reshape(shape), dk.reshape(shape), dv.reshape(shape)
