@@ -1,0 +1,93 @@
+/*
+ * sb_attn.h -- C ABI of the stick-breaking attention library for MI355X (gfx950).
+ *
+ * The operation (paper section 2, Eq. 1), per batch b and head h, 0-based rows:
+ *
+ *     z[i,j] = q_j . k_i / sqrt(d)                       logits
+ *     A[i,j] = sigma(z[i,j]) * prod_{i<k<j} (1 - sigma(z[k,j]))      for i < j
+ *     o_j    = sum_{i<j} A[i,j] v_i                      (o_0 = 0: empty sum)
+ *
+ * evaluated in the log-space form of section 4 (Eq. 2) with a sweep over key
+ * tiles from the diagonal towards key 0 that carries, per query row, the running
+ * sum of softplus(z) (Algorithm 1).  The backward is Eq. 4 / Algorithm 2.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library
+ *     never allocates, frees or keeps device memory and holds no state.
+ *   - Layout [B, H, T, d], contiguous, d fastest.  `m` is [B, H, T].
+ *   - d is 64 or 128; B, H, T >= 1 (any T, not only multiples of the tile);
+ *     B*H*T*d must be below 2^40 elements.
+ *   - Every tensor pointer must be 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void*; NULL means the default stream.
+ *   - Calls only enqueue work: they return after the launch, without a device
+ *     synchronisation.  The return value is an sb_status (0 = ok, negative =
+ *     error, nothing was enqueued).  Nothing is thrown across the boundary.
+ *   - Outputs are written for every row, including the all-zero row j = 0.
+ */
+#ifndef SB_ATTN_H
+#define SB_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SB_OK = 0,
+    SB_ERR_NULL = -1,        /* a required pointer is NULL */
+    SB_ERR_SHAPE = -2,       /* B, H or T < 1, or the tensor is too large */
+    SB_ERR_UNSUPPORTED = -3, /* d is not 64 or 128 */
+    SB_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
+    SB_ERR_LAUNCH = -5,      /* the HIP launch reported an error */
+    SB_ERR_WORKSPACE = -6    /* workspace missing or too small */
+} sb_status;
+
+/*
+ * Forward, Eq. 1 via Algorithm 1.  q, k, v, o: bf16 (16-bit brain float).
+ * Logits, softplus, the carried sums and the output accumulator are fp32; the
+ * weights are rounded to bf16 only as matrix-core operands; o is rounded to
+ * bf16 (nearest even) on store.
+ */
+int sb_attn_fwd(const void* q, const void* k, const void* v, void* o,
+                int B, int H, int T, int d, void* stream);
+
+/*
+ * Training forward: as sb_attn_fwd, and also writes m[b,h,j] (fp32) =
+ * -sum_{i<j} softplus(z[i,j]) = log(1 - sum_i A[i,j]), the vector that
+ * Algorithm 1 stores at its end and Algorithm 2 reads back.  m[.,.,0] = 0.
+ */
+int sb_attn_fwd_train(const void* q, const void* k, const void* v, void* o, float* m,
+                      int B, int H, int T, int d, void* stream);
+
+/*
+ * fp32 forward (fp32 q, k, v, o, optional m; all arithmetic fp32 on the vector
+ * ALU).  m may be NULL.
+ */
+int sb_attn_fwd_f32(const float* q, const float* k, const float* v, float* o, float* m,
+                    int B, int H, int T, int d, void* stream);
+
+/*
+ * Backward, Eq. 4 via Algorithm 2 (with dV = A^T dO and dK = dZ^T Q / sqrt(d)).
+ * q, k, v, dout: bf16.  m: fp32 from sb_attn_fwd_train.  dq, dk, dv: fp32,
+ * fully overwritten (the library clears dk and dv itself before accumulating).
+ * workspace: device scratch of at least sb_attn_bwd_workspace_bytes() bytes
+ * (may be NULL when that returns 0).
+ * The accumulation order of dk/dv across query blocks is not fixed, so two runs
+ * agree to rounding, not bit for bit.
+ */
+size_t sb_attn_bwd_workspace_bytes(int B, int H, int T, int d);
+int sb_attn_bwd(const void* q, const void* k, const void* v, const float* m, const void* dout,
+                float* dq, float* dk, float* dv, void* workspace, size_t workspace_bytes,
+                int B, int H, int T, int d, void* stream);
+
+/* Human-readable name of a status code (static storage). */
+const char* sb_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int sb_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SB_ATTN_H */

@@ -1,0 +1,161 @@
+"""Thin ctypes binding of libsbattn.so (include/sb_attn.h): same names, argument
+marshalling only.  torch is used to own device memory and to name the stream;
+every step of the computation runs inside the library's kernels.
+
+There is no fallback: if the library is missing or a call fails, this raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsbattn.so")
+
+EXPORTS = (
+    "sb_attn_fwd", "sb_attn_fwd_train", "sb_attn_fwd_f32",
+    "sb_attn_bwd_workspace_bytes", "sb_attn_bwd",
+    "sb_status_string", "sb_version",
+)
+
+_lib = None
+
+
+class SbAttnError(RuntimeError):
+    pass
+
+
+def load(build_if_missing: bool = True):
+    """Load libsbattn.so (building it first only when no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise SbAttnError(f"{LIB_PATH} not built; run `python -m paper_2410_17980_amd.build`")
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, fp = ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p
+    lib.sb_attn_fwd.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, vp]
+    lib.sb_attn_fwd.restype = ci
+    lib.sb_attn_fwd_train.argtypes = [vp, vp, vp, vp, fp, ci, ci, ci, ci, vp]
+    lib.sb_attn_fwd_train.restype = ci
+    lib.sb_attn_fwd_f32.argtypes = [fp, fp, fp, fp, fp, ci, ci, ci, ci, vp]
+    lib.sb_attn_fwd_f32.restype = ci
+    lib.sb_attn_bwd_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.sb_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.sb_attn_bwd.argtypes = [vp, vp, vp, fp, vp, fp, fp, fp, vp, ctypes.c_size_t, ci, ci, ci, ci, vp]
+    lib.sb_attn_bwd.restype = ci
+    lib.sb_status_string.argtypes = [ci]
+    lib.sb_status_string.restype = ctypes.c_char_p
+    lib.sb_version.argtypes = []
+    lib.sb_version.restype = ci
+    _lib = lib
+    return lib
+
+
+def sb_status_string(status: int) -> str:
+    return load().sb_status_string(int(status)).decode()
+
+
+def sb_version() -> int:
+    return int(load().sb_version())
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise SbAttnError(f"{what} failed: {sb_status_string(rc)} ({rc})")
+
+
+def _dims(t: torch.Tensor):
+    if t.dim() != 4:
+        raise SbAttnError("expected a [B, H, T, d] tensor")
+    return tuple(int(x) for x in t.shape)
+
+
+def _ptr(t, dtype, shape=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise SbAttnError(f"{name} must live on the GPU")
+    if t.dtype != dtype:
+        raise SbAttnError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise SbAttnError(f"{name} must be contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise SbAttnError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def sb_attn_fwd(q, k, v, o=None, stream=None):
+    """bf16 forward.  Returns o (allocated when not given)."""
+    B, H, T, d = _dims(q)
+    if o is None:
+        o = torch.empty_like(q)
+    rc = load().sb_attn_fwd(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, q.shape, "k"),
+                            _ptr(v, torch.bfloat16, q.shape, "v"), _ptr(o, torch.bfloat16, q.shape, "o"),
+                            B, H, T, d, _stream(stream))
+    _check(rc, "sb_attn_fwd")
+    return o
+
+
+def sb_attn_fwd_train(q, k, v, o=None, m=None, stream=None):
+    """bf16 forward that also returns m[B,H,T] (fp32) for the backward."""
+    B, H, T, d = _dims(q)
+    if o is None:
+        o = torch.empty_like(q)
+    if m is None:
+        m = torch.empty((B, H, T), dtype=torch.float32, device=q.device)
+    rc = load().sb_attn_fwd_train(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, q.shape, "k"),
+                                  _ptr(v, torch.bfloat16, q.shape, "v"), _ptr(o, torch.bfloat16, q.shape, "o"),
+                                  _ptr(m, torch.float32, (B, H, T), "m"), B, H, T, d, _stream(stream))
+    _check(rc, "sb_attn_fwd_train")
+    return o, m
+
+
+def sb_attn_fwd_f32(q, k, v, o=None, m=None, want_m=False, stream=None):
+    """fp32 forward.  Returns o, or (o, m) when m is given or want_m is set."""
+    B, H, T, d = _dims(q)
+    if o is None:
+        o = torch.empty_like(q)
+    if m is None and want_m:
+        m = torch.empty((B, H, T), dtype=torch.float32, device=q.device)
+    rc = load().sb_attn_fwd_f32(_ptr(q, torch.float32, None, "q"), _ptr(k, torch.float32, q.shape, "k"),
+                                _ptr(v, torch.float32, q.shape, "v"), _ptr(o, torch.float32, q.shape, "o"),
+                                _ptr(m, torch.float32, (B, H, T), "m"), B, H, T, d, _stream(stream))
+    _check(rc, "sb_attn_fwd_f32")
+    return (o, m) if m is not None else o
+
+
+def sb_attn_bwd_workspace_bytes(B, H, T, d) -> int:
+    return int(load().sb_attn_bwd_workspace_bytes(B, H, T, d))
+
+
+def sb_attn_bwd(q, k, v, m, dout, dq=None, dk=None, dv=None, workspace=None, stream=None):
+    """bf16 backward.  Returns (dq, dk, dv) in fp32."""
+    B, H, T, d = _dims(q)
+    mk = lambda: torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    dq = mk() if dq is None else dq
+    dk = mk() if dk is None else dk
+    dv = mk() if dv is None else dv
+    need = sb_attn_bwd_workspace_bytes(B, H, T, d)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_ptr = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = load().sb_attn_bwd(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, q.shape, "k"),
+                            _ptr(v, torch.bfloat16, q.shape, "v"), _ptr(m, torch.float32, (B, H, T), "m"),
+                            _ptr(dout, torch.bfloat16, q.shape, "dout"),
+                            _ptr(dq, torch.float32, q.shape, "dq"), _ptr(dk, torch.float32, q.shape, "dk"),
+                            _ptr(dv, torch.float32, q.shape, "dv"), ws_ptr, ws_bytes,
+                            B, H, T, d, _stream(stream))
+    _check(rc, "sb_attn_bwd")
+    return dq, dk, dv

@@ -1,0 +1,101 @@
+// C-ABI entry points: argument validation and dispatch to the kernel launchers.
+// See include/sb_attn.h for the contract of every call.
+#include "../../include/sb_attn.h"
+#include "sb_kernels.h"
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(int B, int H, int T, int d)
+{
+    if (B < 1 || H < 1 || T < 1) return SB_ERR_SHAPE;
+    if (d != 64 && d != 128) return SB_ERR_UNSUPPORTED;
+    const double elems = (double)B * H * (double)T * d;
+    if (elems >= 1099511627776.0 /* 2^40 */ || (double)B * H > 2147483647.0) return SB_ERR_SHAPE;
+    return SB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sb_attn_fwd_train(const void* q, const void* k, const void* v, void* o, float* m,
+                      int B, int H, int T, int d, void* stream);
+
+int sb_attn_fwd(const void* q, const void* k, const void* v, void* o,
+                int B, int H, int T, int d, void* stream)
+{
+    if (!q || !k || !v || !o) return SB_ERR_NULL;
+    if (int rc = check_shape(B, H, T, d)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return SB_ERR_ALIGN;
+    hipError_t e = sb::launch_fwd_bf16(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                                       static_cast<const uint16_t*>(v), static_cast<uint16_t*>(o),
+                                       nullptr, B, H, T, d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
+int sb_attn_fwd_train(const void* q, const void* k, const void* v, void* o, float* m,
+                      int B, int H, int T, int d, void* stream)
+{
+    if (!q || !k || !v || !o || !m) return SB_ERR_NULL;
+    if (int rc = check_shape(B, H, T, d)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(m))
+        return SB_ERR_ALIGN;
+    hipError_t e = sb::launch_fwd_bf16(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                                       static_cast<const uint16_t*>(v), static_cast<uint16_t*>(o),
+                                       m, B, H, T, d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
+int sb_attn_fwd_f32(const float* q, const float* k, const float* v, float* o, float* m,
+                    int B, int H, int T, int d, void* stream)
+{
+    if (!q || !k || !v || !o) return SB_ERR_NULL;
+    if (int rc = check_shape(B, H, T, d)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || (m && !aligned16(m)))
+        return SB_ERR_ALIGN;
+    hipError_t e = sb::launch_fwd_f32(q, k, v, o, m, B, H, T, d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
+size_t sb_attn_bwd_workspace_bytes(int B, int H, int T, int d)
+{
+    (void)B; (void)H; (void)T; (void)d;
+    return 0;
+}
+
+int sb_attn_bwd(const void* q, const void* k, const void* v, const float* m, const void* dout,
+                float* dq, float* dk, float* dv, void* workspace, size_t workspace_bytes,
+                int B, int H, int T, int d, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (!q || !k || !v || !m || !dout || !dq || !dk || !dv) return SB_ERR_NULL;
+    if (int rc = check_shape(B, H, T, d)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(m) || !aligned16(dout) ||
+        !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
+        return SB_ERR_ALIGN;
+    hipError_t e = sb::launch_bwd_bf16(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                                       static_cast<const uint16_t*>(v), m,
+                                       static_cast<const uint16_t*>(dout), dq, dk, dv,
+                                       B, H, T, d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
+const char* sb_status_string(int status)
+{
+    switch (status) {
+    case SB_OK: return "ok";
+    case SB_ERR_NULL: return "null pointer";
+    case SB_ERR_SHAPE: return "bad shape";
+    case SB_ERR_UNSUPPORTED: return "unsupported head dimension (need 64 or 128)";
+    case SB_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case SB_ERR_LAUNCH: return "kernel launch failed";
+    case SB_ERR_WORKSPACE: return "workspace missing or too small";
+    default: return "unknown status";
+    }
+}
+
+int sb_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,21 @@
+// Internal launcher declarations shared by the C-ABI translation unit and the
+// kernel translation units.  Not part of the public interface.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sb {
+
+// Each launcher validates nothing (the C-ABI layer did) and returns the HIP
+// error of the launch.
+hipError_t launch_fwd_f32(const float* q, const float* k, const float* v, float* o, float* m,
+                          int B, int H, int T, int d, hipStream_t stream);
+
+hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o,
+                           float* m, int B, int H, int T, int d, hipStream_t stream);
+
+hipError_t launch_bwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const float* m,
+                           const uint16_t* dout, float* dq, float* dk, float* dv,
+                           int B, int H, int T, int d, hipStream_t stream);
+
+}  // namespace sb

@@ -1,0 +1,70 @@
+"""The C-ABI library loads and exports every symbol the public header declares;
+argument validation returns error codes without touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sb_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(sb_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2410_17980_amd import binding
+    return binding.load()
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    for n in ("sb_attn_fwd", "sb_attn_fwd_train", "sb_attn_fwd_f32", "sb_attn_bwd",
+              "sb_attn_bwd_workspace_bytes", "sb_status_string", "sb_version"):
+        assert n in names
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2410_17980_amd import binding
+    for n in declared_functions():
+        assert hasattr(lib, n), n
+    assert set(binding.EXPORTS) == set(declared_functions())
+
+
+def test_version_and_status_strings(lib):
+    from paper_2410_17980_amd import binding
+    assert binding.sb_version() >= 100
+    assert binding.sb_status_string(0) == "ok"
+    seen = {binding.sb_status_string(c) for c in range(-6, 1)}
+    assert len(seen) == 7
+    assert binding.sb_status_string(-99) == "unknown status"
+
+
+def test_argument_validation_without_a_gpu(lib):
+    p = ctypes.c_void_p(4096)          # never dereferenced: validation fails first
+    odd = ctypes.c_void_p(4096 + 8)
+    assert lib.sb_attn_fwd(None, p, p, p, 1, 1, 8, 64, None) == -1
+    assert lib.sb_attn_fwd(p, p, p, None, 1, 1, 8, 64, None) == -1
+    assert lib.sb_attn_fwd(p, p, p, p, 0, 1, 8, 64, None) == -2
+    assert lib.sb_attn_fwd(p, p, p, p, 1, 1, 0, 64, None) == -2
+    assert lib.sb_attn_fwd(p, p, p, p, 1, 1, 8, 96, None) == -3
+    assert lib.sb_attn_fwd(p, odd, p, p, 1, 1, 8, 64, None) == -4
+    assert lib.sb_attn_fwd(p, p, p, p, 1 << 20, 1 << 10, 1 << 12, 128, None) == -2
+    assert lib.sb_attn_fwd_train(p, p, p, p, None, 1, 1, 8, 64, None) == -1
+    assert lib.sb_attn_fwd_f32(p, p, None, p, None, 1, 1, 8, 64, None) == -1
+    assert lib.sb_attn_fwd_f32(p, p, p, p, odd, 1, 1, 8, 64, None) == -4
+    assert lib.sb_attn_bwd(p, p, p, None, p, p, p, p, None, 0, 1, 1, 8, 64, None) == -1
+    assert lib.sb_attn_bwd(p, p, p, p, p, p, p, p, None, 0, 1, 1, 8, 32, None) == -3
+
+
+def test_binding_fails_loudly_on_cpu_tensors():
+    import torch
+    from paper_2410_17980_amd import binding
+    x = torch.zeros(1, 1, 4, 64, dtype=torch.bfloat16)
+    with pytest.raises(binding.SbAttnError):
+        binding.sb_attn_fwd(x, x, x, x)

@@ -1,0 +1,180 @@
+"""GPU parity: the HIP forward (through the C ABI) against the CPU float64 oracle
+on the same seeded, already-rounded inputs.
+
+Tolerances (max abs error on o): 1e-5 for the fp32 path, 2e-2 for the bf16 path
+(bf16 inputs, fp32 accumulation, weights rounded to bf16 as matrix operands).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import BF16_TOL, F32_TOL, check_m, dev, max_abs, to64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sb():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2410_17980_amd import binding
+    binding.load(build_if_missing=False)      # the built library must be there
+    return binding
+
+
+@pytest.fixture(scope="module")
+def gen():
+    from paper_2410_17980_amd import inputs
+    return inputs
+
+
+def run_bf16(sb, oracle, q, k, v, tol=BF16_TOL, rows=None):
+    qd, kd, vd = dev(q, k, v)
+    o, m = sb.sb_attn_fwd_train(qd, kd, vd)
+    o2 = sb.sb_attn_fwd(qd, kd, vd)
+    torch.cuda.synchronize()
+    assert torch.equal(o, o2), "fwd and fwd_train must give the same o"
+    ref, rem = oracle.fwd(to64(q), to64(k), to64(v), rows=rows)
+    og, mg = to64(o), to64(m)
+    if rows is not None:
+        og, mg = og[..., rows[0]:rows[1], :], mg[..., rows[0]:rows[1]]
+    assert np.all(np.isfinite(og))
+    err = max_abs(og, ref)
+    assert err <= tol, f"max abs err {err}"
+    check_m(mg, rem)
+    return err
+
+
+# ------------------------------------------------------------------ fp32 path
+def test_f32_workload_1(sb, oracle, gen):
+    w = gen.WORKLOADS[0]
+    q, k, v = gen.workload_tensors(w)
+    qd, kd, vd = dev(q, k, v)
+    o, m = sb.sb_attn_fwd_f32(qd, kd, vd, want_m=True)
+    torch.cuda.synchronize()
+    ref, rem = oracle.fwd(to64(q), to64(k), to64(v))
+    assert max_abs(to64(o), ref) <= F32_TOL
+    check_m(to64(m), rem, rtol=1e-5, atol=1e-5)
+    assert not to64(o)[0, 0, 0].any()
+
+
+@pytest.mark.parametrize("T", [1, 2, 31, 64, 65, 200, 257])
+@pytest.mark.parametrize("d", [64, 128])
+def test_f32_shapes(sb, oracle, gen, T, d):
+    q, k, v = gen.gaussian(2, 3, T, d, seed=100 + T, dtype="f32")
+    qd, kd, vd = dev(q, k, v)
+    o = sb.sb_attn_fwd_f32(qd, kd, vd)
+    torch.cuda.synchronize()
+    ref, _ = oracle.fwd(to64(q), to64(k), to64(v))
+    assert max_abs(to64(o), ref) <= F32_TOL
+
+
+def test_f32_long_range_and_sharp(sb, oracle, gen):
+    for q, k, v in (gen.constant_logit(1, 2, 700, 64, 5, kval=-48.0, dtype="f32"),
+                    gen.biased_gaussian(1, 2, 600, 64, 6, shift=-6.0, dtype="f32"),
+                    gen.scaled_gaussian(1, 2, 300, 128, 7, gain=30.0, dtype="f32")):
+        qd, kd, vd = dev(q, k, v)
+        o, m = sb.sb_attn_fwd_f32(qd, kd, vd, want_m=True)
+        torch.cuda.synchronize()
+        ref, rem = oracle.fwd(to64(q), to64(k), to64(v))
+        # long sums of softplus in fp32: allow the carry's rounding, 2^-24 * |sum| per step
+        assert max_abs(to64(o), ref) <= 5e-5
+        check_m(to64(m), rem, rtol=1e-5, atol=1e-5)
+
+
+# ------------------------------------------------------------------ bf16 path
+@pytest.mark.parametrize("T", [1, 2, 31, 32, 33, 64, 100, 127, 128, 129, 300, 517])
+@pytest.mark.parametrize("d", [64, 128])
+def test_bf16_shapes(sb, oracle, gen, T, d):
+    q, k, v = gen.gaussian(2, 3, T, d, seed=200 + T + d, dtype="bf16")
+    run_bf16(sb, oracle, q, k, v)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_bf16_first_row_is_zero_and_deterministic(sb, gen, d):
+    q, k, v = dev(*gen.gaussian(3, 5, 333, d, seed=9, dtype="bf16"))
+    o1, m1 = sb.sb_attn_fwd_train(q, k, v)
+    o2, m2 = sb.sb_attn_fwd_train(q, k, v)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(m1, m2)
+    assert not o1[:, :, 0].any() and not m1[:, :, 0].any()
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_bf16_constant_logit_long_range(sb, oracle, gen, d):
+    """Small equal sigma everywhere: weights reach across many key tiles, so a
+    wrong cross-tile carry cannot hide.  Closed form: A = b (1-b)^(j-i-1)."""
+    T = 1100
+    kval = -48.0 if d == 64 else -64.0
+    q, k, v = gen.constant_logit(1, 2, T, d, seed=3, kval=kval, dtype="bf16")
+    run_bf16(sb, oracle, q, k, v)
+    # and directly against the closed form, independent of the oracle
+    o = to64(sb.sb_attn_fwd(*dev(q, k, v)))
+    b = 1.0 / (1.0 + math.exp(-kval / math.sqrt(d)))
+    j, i = np.meshgrid(np.arange(T), np.arange(T), indexing="ij")
+    A = np.where(i < j, b * (1.0 - b) ** np.clip(j - i - 1, 0, None), 0.0)
+    assert max_abs(o[0, 0], A @ to64(v)[0, 0]) <= BF16_TOL
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_bf16_biased_long_range(sb, oracle, gen, d):
+    q, k, v = gen.biased_gaussian(1, 3, 900, d, seed=4, shift=-6.0, dtype="bf16")
+    run_bf16(sb, oracle, q, k, v)
+
+
+@pytest.mark.parametrize("gain", [3.0, 30.0, 1000.0])
+def test_bf16_sharp_logits(sb, oracle, gen, gain):
+    """Near-saturated sigma: the stability path (no overflow, no NaN)."""
+    q, k, v = gen.scaled_gaussian(1, 2, 400, 128, seed=5, gain=gain, dtype="bf16")
+    run_bf16(sb, oracle, q, k, v)
+
+
+def test_bf16_hugely_negative_logits_attend_to_nothing(sb, gen):
+    q, k, v = gen.constant_logit(1, 1, 200, 64, seed=1, kval=-4096.0, dtype="bf16")
+    o, m = sb.sb_attn_fwd_train(*dev(q, k, v))
+    torch.cuda.synchronize()
+    assert not o.any() and not m.any()
+
+
+# ------------------------------------------------ the paper-shaped workloads
+def test_workload_2_sampled_heads(sb, oracle, gen):
+    w = gen.WORKLOADS[1]
+    q, k, v = gen.workload_tensors(w)
+    qd, kd, vd = dev(q, k, v)
+    o, m = sb.sb_attn_fwd_train(qd, kd, vd)
+    torch.cuda.synchronize()
+    for b, h in gen.slice_picks(w, 4):
+        ref, rem = oracle.fwd(to64(q[b, h]), to64(k[b, h]), to64(v[b, h]))
+        assert max_abs(to64(o[b, h]), ref) <= BF16_TOL
+        check_m(to64(m[b, h]), rem)
+
+
+def test_workload_3_headline_sampled_heads(sb, oracle, gen):
+    w = gen.WORKLOADS[2]
+    q, k, v = gen.workload_tensors(w)
+    qd, kd, vd = dev(q, k, v)
+    o, m = sb.sb_attn_fwd_train(qd, kd, vd)
+    torch.cuda.synchronize()
+    picks = gen.slice_picks(w, 4)
+    assert sum(h >= w.H // 2 for _, h in picks) >= 2          # sharp heads are covered
+    for b, h in picks:
+        ref, rem = oracle.fwd(to64(q[b, h]), to64(k[b, h]), to64(v[b, h]))
+        assert max_abs(to64(o[b, h]), ref) <= BF16_TOL
+        check_m(to64(m[b, h]), rem)
+    # properties that hold at any size
+    of = o.float()
+    assert torch.isfinite(of).all() and not of[:, :, 0].any()
+    assert (m <= 0).all()
+
+
+def test_workload_5_long_context_tail_rows(sb, oracle, gen):
+    w = gen.WORKLOADS[4]
+    q, k, v = gen.workload_tensors(w)
+    qd, kd, vd = dev(q, k, v)
+    o = sb.sb_attn_fwd(qd, kd, vd)
+    torch.cuda.synchronize()
+    r0, r1 = w.T - 512, w.T
+    for b, h in gen.slice_picks(w, 2):
+        ref, _ = oracle.fwd(to64(q[b, h]), to64(k[b, h]), to64(v[b, h]), rows=(r0, r1))
+        assert max_abs(to64(o[b, h, r0:r1]), ref) <= BF16_TOL
