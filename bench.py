@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the stick-breaking attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one pass of the hot path over one synthetic batch of the headline
+workload (bf16, B=8, H=16, T=4096, d_head=128; half the heads with k*3): the
+training forward (o and m) followed by the backward (dq, dk, dv).  Inputs are
+resident in HBM before the timed region starts.  One JSON line is printed:
+whole-step TFLOP/s as `value`, the forward and backward separately, a roofline
+object for the dominant kernel and the CPU oracle timed on a bounded sample.
+
+FLOP convention (algorithmic, strictly causal pairs only): one contraction is
+2*d FLOP per (query, key) pair with key < query; forward = 2 contractions,
+backward = 5.  Nothing else (masked halves of diagonal tiles, recomputation,
+element-wise work) is counted.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak (published)
+DEFAULT_PASSES = "fwd"        # the backward kernel has not landed yet
+
+
+def flops_fwd(B, H, T, d):
+    return 2.0 * B * H * d * T * (T - 1)
+
+
+def flops_bwd(B, H, T, d):
+    return 5.0 * B * H * d * T * (T - 1)
+
+
+def event_time_ms(fn, iters):
+    """Average duration of fn() over iters back-to-back launches, HIP events on
+    the stream the kernels are launched on (torch's current stream)."""
+    import torch
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def cpu_baseline(w, q, k, v, dout, n_heads, with_bwd):
+    """The float64 oracle, as it stands, on n_heads (b, h) slices of the workload:
+    forward and backward.  Reported in the metric's unit with the same FLOP formula."""
+    from oracle import sb_oracle
+    from paper_2410_17980_amd import inputs
+    import torch
+    sb_oracle.build()
+    picks = inputs.slice_picks(w, n_heads)
+    f64 = lambda t: t.to(torch.float32).to(torch.float64).numpy()
+    qs, ks, vs, gs = ([f64(t[b, h]) for b, h in picks] for t in (q, k, v, dout))
+    t0 = time.perf_counter()
+    for i in range(n_heads):
+        sb_oracle.fwd(qs[i], ks[i], vs[i])
+    t1 = time.perf_counter()
+    if with_bwd:
+        for i in range(n_heads):
+            sb_oracle.bwd(qs[i], ks[i], vs[i], gs[i])
+    t2 = time.perf_counter()
+    fl = n_heads * (flops_fwd(1, 1, w.T, w.d) + (flops_bwd(1, 1, w.T, w.d) if with_bwd else 0.0))
+    return {
+        "value": fl / (t2 - t0) / 1e12,
+        "unit": "TFLOP/s",
+        "cores": sb_oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"{n_heads} (b,h) slices of the workload, fwd {t1 - t0:.2f} s + bwd {t2 - t1:.2f} s, float64",
+        "fwd_tflops": n_heads * flops_fwd(1, 1, w.T, w.d) / (t1 - t0) / 1e12,
+        "bwd_tflops": n_heads * flops_bwd(1, 1, w.T, w.d) / (t2 - t1) / 1e12 if with_bwd else None,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--cpu-heads", type=int, default=6, help="(b,h) slices the CPU oracle is timed on; 0 = skip")
+    ap.add_argument("--kernel-iters", type=int, default=20, help="launches per kernel for the event timing")
+    ap.add_argument("--passes", choices=["fwd", "fwd+bwd"], default=DEFAULT_PASSES,
+                    help="what one step runs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (batch and heads shard "
+                 "without communication, so N GPUs would each run this same kernel on B/N).")
+
+    import torch
+    from paper_2410_17980_amd import binding as sb
+    from paper_2410_17980_amd import inputs
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    sb.load(build_if_missing=True)
+    torch.cuda.set_device(0)
+
+    w = inputs.WORKLOADS[2]
+    B, H, T, d = w.B, w.H, w.T, w.d
+    q, k, v, dout = inputs.gaussian(B, H, T, d, w.seed, w.dtype, w.sharp_half, with_dout=True)
+    qd, kd, vd, gd = (t.cuda() for t in (q, k, v, dout))
+    o = torch.empty_like(qd)
+    m = torch.empty((B, H, T), dtype=torch.float32, device="cuda")
+    dq = torch.empty((B, H, T, d), dtype=torch.float32, device="cuda")
+    dk = torch.empty_like(dq)
+    dv = torch.empty_like(dq)
+
+    def fwd():
+        sb.sb_attn_fwd_train(qd, kd, vd, o, m)
+
+    def bwd():
+        sb.sb_attn_bwd(qd, kd, vd, m, gd, dq, dk, dv)
+
+    with_bwd = args.passes == "fwd+bwd"
+
+    def step():
+        fwd()
+        if with_bwd:
+            bwd()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    f_fwd, f_bwd = flops_fwd(B, H, T, d), flops_bwd(B, H, T, d)
+    ms_fwd = event_time_ms(fwd, args.kernel_iters)
+    ms_bwd = event_time_ms(bwd, args.kernel_iters) if with_bwd else 0.0
+    tf_fwd = f_fwd / (ms_fwd * 1e-3) / 1e12
+    tf_bwd = f_bwd / (ms_bwd * 1e-3) / 1e12 if with_bwd else 0.0
+    value = (f_fwd + (f_bwd if with_bwd else 0.0)) / (ms_per_step * 1e-3) / 1e12
+
+    # dominant kernel = the one with the larger share of the step
+    if with_bwd and ms_bwd >= ms_fwd:
+        dom, dom_tf, dom_ms = "sb_attn_bwd (bwd_bf16_kernel)", tf_bwd, ms_bwd
+    else:
+        dom, dom_tf, dom_ms = "sb_attn_fwd_train (fwd_bf16_kernel)", tf_fwd, ms_fwd
+
+    out = {
+        "metric": "stick-breaking attn fwd/bwd TFLOP/s + % bf16 MFMA peak, B8 H16 T4096 d128",
+        "value": value,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": B, "H": H, "T": T, "d_head": d,
+                   "inputs": "iid N(0,1) bf16, heads h>=H/2 with k*3, seed 2",
+                   "step": "fwd_train + bwd" if with_bwd else "fwd_train", "early_halt": "off"},
+        "fwd": {"ms": ms_fwd, "tflops": tf_fwd, "frac_bf16_peak": tf_fwd / PEAK_BF16_TFLOPS},
+        "bwd": {"ms": ms_bwd, "tflops": tf_bwd, "frac_bf16_peak": tf_bwd / PEAK_BF16_TFLOPS} if with_bwd else None,
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": dom_tf, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": dom_tf / PEAK_BF16_TFLOPS, "avg_launch_ms": dom_ms,
+                     "traffic": None},
+    }
+    if args.cpu_heads > 0:
+        out["cpu_baseline"] = cpu_baseline(w, q, k, v, dout, args.cpu_heads, with_bwd)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
