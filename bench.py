@@ -27,7 +27,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak (published)
-DEFAULT_PASSES = "fwd"        # the backward kernel has not landed yet
+DEFAULT_PASSES = "fwd+bwd"
 
 
 def flops_fwd(B, H, T, d):
@@ -87,7 +87,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--cpu-heads", type=int, default=6, help="(b,h) slices the CPU oracle is timed on; 0 = skip")
+    ap.add_argument("--cpu-heads", type=int, default=8, help="(b,h) slices the CPU oracle is timed on; 0 = skip")
     ap.add_argument("--kernel-iters", type=int, default=20, help="launches per kernel for the event timing")
     ap.add_argument("--passes", choices=["fwd", "fwd+bwd"], default=DEFAULT_PASSES,
                     help="what one step runs")

@@ -1,0 +1,126 @@
+"""GPU parity: the HIP backward (through the C ABI) against the CPU float64
+oracle's analytic gradients (themselves pinned by finite differences) on the
+same seeded, already-rounded bf16 inputs.
+
+Tolerance: max abs error max(2e-2, 2^-8 * max|ref|) on each of dq, dk, dv: the
+forward's bound while the gradients are O(1), and one bf16 rounding step of the
+largest gradient entry when they are larger (the weights A and the logit
+gradients dZ enter the matrix cores rounded to bf16, so every gradient entry
+carries a relative error of that order whatever its size).
+"""
+import numpy as np
+import pytest
+import torch
+
+from helpers import BF16_TOL, dev, max_abs, to64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sb():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2410_17980_amd import binding
+    binding.load(build_if_missing=False)
+    return binding
+
+
+@pytest.fixture(scope="module")
+def gen():
+    from paper_2410_17980_amd import inputs
+    return inputs
+
+
+def gpu_grads(sb, q, k, v, g):
+    qd, kd, vd, gd = dev(q, k, v, g)
+    o, m = sb.sb_attn_fwd_train(qd, kd, vd)
+    dq, dk, dv = sb.sb_attn_bwd(qd, kd, vd, m, gd)
+    torch.cuda.synchronize()
+    return to64(dq), to64(dk), to64(dv)
+
+
+def grad_tol(ref):
+    return max(BF16_TOL, 2.0 ** -8 * float(np.abs(ref).max()))
+
+
+def check(sb, oracle, q, k, v, g):
+    dq, dk, dv = gpu_grads(sb, q, k, v, g)
+    rq, rk, rv = oracle.bwd(to64(q), to64(k), to64(v), to64(g))
+    errs = {}
+    for name, a, r in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+        assert np.all(np.isfinite(a)), name
+        errs[name] = max_abs(a, r)
+        print(f"{name}: err {errs[name]:.3e} max|ref| {np.abs(r).max():.3e} tol {grad_tol(r):.3e}")
+        assert errs[name] <= grad_tol(r), f"{name}: max abs err {errs[name]} (max |ref| {np.abs(r).max()})"
+    return errs
+
+
+@pytest.mark.parametrize("T", [1, 2, 32, 33, 64, 100, 129, 300])
+@pytest.mark.parametrize("d", [64, 128])
+def test_bwd_shapes(sb, oracle, gen, T, d):
+    q, k, v, g = gen.gaussian(2, 3, T, d, seed=300 + T + d, dtype="bf16", with_dout=True)
+    check(sb, oracle, q, k, v, g)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_bwd_finite_differences_T32(sb, oracle, gen, d):
+    """Directional finite differences of the float64 forward at T = 32 against
+    the GPU gradients (independent of the oracle's own backward)."""
+    q, k, v, g = gen.gaussian(1, 1, 32, d, seed=77, dtype="bf16", with_dout=True)
+    dq, dk, dv = gpu_grads(sb, q, k, v, g)
+    q64, k64, v64, g64 = (to64(t)[0, 0] for t in (q, k, v, g))
+    loss = lambda a, b, c: float((oracle.fwd(a, b, c)[0] * g64).sum())
+    rng = np.random.default_rng(0)
+    h = 1e-5
+    for _ in range(6):
+        uq, uk, uv = (rng.standard_normal(q64.shape) for _ in range(3))
+        fd = (loss(q64 + h * uq, k64 + h * uk, v64 + h * uv) -
+              loss(q64 - h * uq, k64 - h * uk, v64 - h * uv)) / (2 * h)
+        an = float((dq[0, 0] * uq).sum() + (dk[0, 0] * uk).sum() + (dv[0, 0] * uv).sum())
+        norm = np.sqrt((dq ** 2).sum() + (dk ** 2).sum() + (dv ** 2).sum()) * np.sqrt(3 * q64.size)
+        assert abs(fd - an) <= 2e-3 * norm + 1e-3, (fd, an)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_bwd_long_range(sb, oracle, gen, d):
+    """Slowly decaying weights: the carries a and b cross many key tiles."""
+    kval = -48.0 if d == 64 else -64.0
+    q, k, v, g = gen.constant_logit(1, 2, 700, d, seed=13, kval=kval, dtype="bf16", with_dout=True)
+    check(sb, oracle, q, k, v, g)
+    q, k, v, g = gen.biased_gaussian(1, 2, 700, d, seed=14, shift=-6.0, dtype="bf16", with_dout=True)
+    check(sb, oracle, q, k, v, g)
+
+
+@pytest.mark.parametrize("gain", [3.0, 30.0])
+def test_bwd_sharp_logits(sb, oracle, gen, gain):
+    q, k, v, g = gen.scaled_gaussian(1, 2, 300, 128, seed=15, gain=gain, dtype="bf16", with_dout=True)
+    check(sb, oracle, q, k, v, g)
+
+
+def test_bwd_twice_agrees_and_overwrites(sb, gen):
+    q, k, v, g = dev(*gen.gaussian(2, 4, 257, 128, seed=16, dtype="bf16", with_dout=True))
+    o, m = sb.sb_attn_fwd_train(q, k, v)
+    junk = lambda: torch.full(q.shape, 123.0, dtype=torch.float32, device="cuda")
+    dq1, dk1, dv1 = sb.sb_attn_bwd(q, k, v, m, g, junk(), junk(), junk())
+    dq2, dk2, dv2 = sb.sb_attn_bwd(q, k, v, m, g, junk(), junk(), junk())
+    torch.cuda.synchronize()
+    assert torch.equal(dq1, dq2)                       # no atomics on dq
+    assert (dk1 - dk2).abs().max() <= 1e-4 and (dv1 - dv2).abs().max() <= 1e-4
+    assert not dk1[:, :, -1].any() and not dv1[:, :, -1].any()   # last key: no later query
+    assert not dq1[:, :, 0].any()                                 # first query: no earlier key
+
+
+def test_workload_4_sampled_heads(sb, oracle, gen):
+    w = gen.WORKLOADS[3]
+    q, k, v, g = gen.workload_tensors(w)
+    qd, kd, vd, gd = dev(q, k, v, g)
+    o, m = sb.sb_attn_fwd_train(qd, kd, vd)
+    dq, dk, dv = sb.sb_attn_bwd(qd, kd, vd, m, gd)
+    torch.cuda.synchronize()
+    for b, h in gen.slice_picks(w, 4):
+        rq, rk, rv = oracle.bwd(to64(q[b, h]), to64(k[b, h]), to64(v[b, h]), to64(g[b, h]))
+        for name, a, r in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+            err = max_abs(to64(a[b, h]), r)
+            print(f"{name}[{b},{h}]: err {err:.3e} max|ref| {np.abs(r).max():.3e}")
+            assert err <= grad_tol(r), f"{name}[{b},{h}]: {err} (max |ref| {np.abs(r).max()})"
+    assert torch.isfinite(dq).all() and torch.isfinite(dk).all() and torch.isfinite(dv).all()
