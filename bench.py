@@ -114,12 +114,13 @@ def main():
     dq = torch.empty((B, H, T, d), dtype=torch.float32, device="cuda")
     dk = torch.empty_like(dq)
     dv = torch.empty_like(dq)
+    ws = torch.empty(sb.sb_attn_bwd_workspace_bytes(B, H, T, d), dtype=torch.uint8, device="cuda")
 
     def fwd():
         sb.sb_attn_fwd_train(qd, kd, vd, o, m)
 
     def bwd():
-        sb.sb_attn_bwd(qd, kd, vd, m, gd, dq, dk, dv)
+        sb.sb_attn_bwd(qd, kd, vd, m, gd, dq, dk, dv, ws)
 
     with_bwd = args.passes == "fwd+bwd"
 

@@ -68,13 +68,16 @@ int sb_attn_fwd_f32(const float* q, const float* k, const float* v, float* o, fl
                     int B, int H, int T, int d, void* stream);
 
 /*
- * Backward, Eq. 4 via Algorithm 2 (with dV = A^T dO and dK = dZ^T Q / sqrt(d)).
+ * Backward, Eq. 4 with the per-tile steps of Algorithm 2 (dV = A^T dO,
+ * dK = dZ^T Q / sqrt(d), dQ = dZ K / sqrt(d)).
  * q, k, v, dout: bf16.  m: fp32 from sb_attn_fwd_train.  dq, dk, dv: fp32,
- * fully overwritten (the library clears dk and dv itself before accumulating).
- * workspace: device scratch of at least sb_attn_bwd_workspace_bytes() bytes
- * (may be NULL when that returns 0).
- * The accumulation order of dk/dv across query blocks is not fixed, so two runs
- * agree to rounding, not bit for bit.
+ * fully overwritten (no need to clear them).
+ * workspace: caller-owned device scratch of at least
+ * sb_attn_bwd_workspace_bytes(B,H,T,d) bytes, 16-byte aligned; its contents on
+ * entry do not matter and are garbage afterwards.  It holds two floats per
+ * (query row, 32-key strip): 8*B*H*T*ceil(T/32) bytes.  SB_ERR_WORKSPACE if it
+ * is NULL or too small.  sb_attn_bwd_workspace_bytes returns 0 for a bad shape.
+ * No atomics are used: results are bit-reproducible from run to run.
  */
 size_t sb_attn_bwd_workspace_bytes(int B, int H, int T, int d);
 int sb_attn_bwd(const void* q, const void* k, const void* v, const float* m, const void* dout,

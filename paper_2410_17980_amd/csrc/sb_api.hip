@@ -61,23 +61,24 @@ int sb_attn_fwd_f32(const float* q, const float* k, const float* v, float* o, fl
 
 size_t sb_attn_bwd_workspace_bytes(int B, int H, int T, int d)
 {
-    (void)B; (void)H; (void)T; (void)d;
-    return 0;
+    if (check_shape(B, H, T, d) != SB_OK) return 0;
+    return sb::bwd_workspace_bytes(B, H, T);
 }
 
 int sb_attn_bwd(const void* q, const void* k, const void* v, const float* m, const void* dout,
                 float* dq, float* dk, float* dv, void* workspace, size_t workspace_bytes,
                 int B, int H, int T, int d, void* stream)
 {
-    (void)workspace; (void)workspace_bytes;
     if (!q || !k || !v || !m || !dout || !dq || !dk || !dv) return SB_ERR_NULL;
     if (int rc = check_shape(B, H, T, d)) return rc;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(m) || !aligned16(dout) ||
-        !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
+        !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
         return SB_ERR_ALIGN;
+    if (!workspace || workspace_bytes < sb::bwd_workspace_bytes(B, H, T)) return SB_ERR_WORKSPACE;
     hipError_t e = sb::launch_bwd_bf16(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                                        static_cast<const uint16_t*>(v), m,
                                        static_cast<const uint16_t*>(dout), dq, dk, dv,
+                                       static_cast<float*>(workspace),
                                        B, H, T, d, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
 }

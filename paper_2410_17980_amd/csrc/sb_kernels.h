@@ -2,6 +2,7 @@
 // kernel translation units.  Not part of the public interface.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 namespace sb {
@@ -14,8 +15,10 @@ hipError_t launch_fwd_f32(const float* q, const float* k, const float* v, float*
 hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o,
                            float* m, int B, int H, int T, int d, hipStream_t stream);
 
+// workspace: bwd_workspace_bytes(B, H, T) bytes of device memory, 16-byte aligned
+size_t bwd_workspace_bytes(int B, int H, int T);
 hipError_t launch_bwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const float* m,
-                           const uint16_t* dout, float* dq, float* dk, float* dv,
+                           const uint16_t* dout, float* dq, float* dk, float* dv, float* workspace,
                            int B, int H, int T, int d, hipStream_t stream);
 
 }  // namespace sb

@@ -1,0 +1,87 @@
+// Device-side building blocks shared by the bf16 kernels: vector types, the
+// base-2 softplus, LDS swizzles and the transposing-load helper.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sb {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+#define SB_LDS(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+constexpr float SB_LOG2E = 1.4426950408889634f;
+constexpr float SB_LN2 = 0.6931471805599453f;
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// sp2(x) = log2(1 + 2^x), the base-2 softplus: -sp2 is log2(1 - sigma(z)) and
+// x - sp2 is log2(sigma(z)) for x = z*log2(e).  For x > 128 the power overflows
+// to +inf and so does the log; the true value is then x itself to fp32
+// precision, and the median of (log, x, 128) picks it.  Below that the log
+// lies between x and 128 and is the median.  x = -inf gives 0.
+__device__ __forceinline__ float sp2(float x)
+{
+    return __builtin_amdgcn_fmed3f(fast_log2(1.0f + fast_exp2(x)), x, 128.0f);
+}
+
+// MFMA 32x32 accumulator register r of lane (n, hh) is output row
+// 8*(r/4) + 4*hh + r%4.  Feeding MFMA row rho from tile row perm_row(rho)
+// makes lane (n, hh) own the 16 CONSECUTIVE tile rows 16*hh + r, r = 0..15.
+__device__ __forceinline__ int perm_row(int rho)
+{
+    return 16 * ((rho >> 2) & 1) + 4 * (rho >> 3) + (rho & 3);
+}
+
+// LDS tiles are [row][D] bf16, unpadded, with the 16-byte chunk index of a row
+// xor-ed by a function of the row so that both access patterns are conflict free:
+//   (a) A/B-operand reads: 16 lanes read the same chunk of 16 different rows;
+//   (b) transposing reads: 16 lanes read 32 B of each of 4 consecutive rows,
+//       and the two quarter-waves of a half-wave the other 32 B of the same 64 B.
+// swz_perm is for tiles whose operand reads go through perm_row (the 16 rows are
+// {0..7, 16..23} + 8k), swz_nat for tiles read in natural row order (rows 0..15 + 16k).
+template <int D> __device__ __forceinline__ int swz_perm(int row)
+{
+    if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 1) | (((row >> 4) & 1) << 1);
+    return (((row >> 1) & 1) << 2) | ((row >> 2) & 1) | (((row >> 4) & 1) << 1);
+}
+template <int D> __device__ __forceinline__ int swz_nat(int row)
+{
+    if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+    return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+}
+
+// byte offset of 16-byte chunk c of tile row `row`
+template <int D> __device__ __forceinline__ int tile_off_perm(int row, int c)
+{
+    return row * (D * 2) + ((c ^ swz_perm<D>(row)) << 4);
+}
+template <int D> __device__ __forceinline__ int tile_off_nat(int row, int c)
+{
+    return row * (D * 2) + ((c ^ swz_nat<D>(row)) << 4);
+}
+
+// Two transposing loads (ds_read_b64_tr_b16) glued into one MFMA operand: the
+// K-dimension elements 0..3 come from p_lo, 4..7 from p_hi.  Within each group of
+// 16 lanes, lane i supplies the address of row i/4, columns 4*(i%4)..+3 and
+// receives column i of the four rows.
+__device__ __forceinline__ bf16x8 tr_pair(const char* p_lo, const char* p_hi)
+{
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SB_LDS(s16x4, p_lo));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SB_LDS(s16x4, p_hi));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// both half-waves' copies of a per-lane float: returns (value of lane n, value of lane n+32)
+__device__ __forceinline__ void both_halves(float v, float& lo, float& hi)
+{
+    auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(int, v), __builtin_bit_cast(int, v), false, false);
+    lo = __builtin_bit_cast(float, (int)sw[0]);
+    hi = __builtin_bit_cast(float, (int)sw[1]);
+}
+
+}  // namespace sb

@@ -60,6 +60,13 @@ def test_argument_validation_without_a_gpu(lib):
     assert lib.sb_attn_fwd_f32(p, p, p, p, odd, 1, 1, 8, 64, None) == -4
     assert lib.sb_attn_bwd(p, p, p, None, p, p, p, p, None, 0, 1, 1, 8, 64, None) == -1
     assert lib.sb_attn_bwd(p, p, p, p, p, p, p, p, None, 0, 1, 1, 8, 32, None) == -3
+    # workspace: size query, then missing / too small / misaligned workspace
+    need = lib.sb_attn_bwd_workspace_bytes(2, 3, 100, 64)
+    assert need == 8 * 2 * 3 * 100 * 4          # two floats per (row, 32-key strip)
+    assert lib.sb_attn_bwd_workspace_bytes(2, 3, 100, 65) == 0
+    assert lib.sb_attn_bwd(p, p, p, p, p, p, p, p, None, 0, 2, 3, 100, 64, None) == -6
+    assert lib.sb_attn_bwd(p, p, p, p, p, p, p, p, p, need - 1, 2, 3, 100, 64, None) == -6
+    assert lib.sb_attn_bwd(p, p, p, p, p, p, p, p, odd, need, 2, 3, 100, 64, None) == -4
 
 
 def test_binding_fails_loudly_on_cpu_tensors():
