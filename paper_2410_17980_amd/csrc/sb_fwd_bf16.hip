@@ -1,89 +1,77 @@
 // bf16 forward of causal stick-breaking attention on the gfx950 matrix cores.
 //
-// Work split.  A workgroup (4 wavefronts) owns 128 query rows of one (batch,
-// head); each wavefront owns 32 of them.  Key/value tiles of 64 rows are staged
-// in LDS (double buffered) and swept from the diagonal towards key 0, which is
-// the order Algorithm 1 prescribes: the weight of key i needs the sum of
-// softplus(z) over the keys between i and the query (Eq. 2), so that sum is
-// carried per query row from tile to tile (the vector `a` of Algorithm 1).
+// Work split.  A workgroup (4 wavefronts) owns 128*NG query rows of one (batch,
+// head); each wavefront owns NG groups of 32 of them and keeps their Q fragments
+// in registers (NG = 2 at d = 128: every K / V fragment read from LDS then feeds
+// two MFMAs, and the wave has two independent element-wise streams to interleave
+// with the matrix pipe; the 512-register budget of one wave per SIMD holds it).
+// Keys are swept in 32-row subtiles from the diagonal towards key 0, the order
+// Algorithm 1 prescribes: the weight of key i needs the sum of softplus(z) over
+// the keys between i and the query (Eq. 2), so that sum is carried per query row
+// from subtile to subtile (the vector `a` of Algorithm 1).
 //
 // Layout inside a wavefront.  Logits are formed transposed, S^T = K Q^T, with
 // the 32x32x16 bf16 MFMA: A operand = 32 key rows from LDS, B operand = the
-// wave's 32 query rows held in registers for the whole kernel.  In the MFMA
-// accumulator a lane then owns ONE query column (lane % 32) and 16 key rows.
-// The LDS row fed to MFMA row rho is chosen so that those 16 keys are
-// consecutive: lanes 0-31 hold keys 0..15 of the 32-key subtile, lanes 32-63
-// keys 16..31.  The right-to-left cumulative sum of softplus is therefore a
-// serial add inside the lane plus one exchange with the partner lane
-// (v_permlane32_swap), and the row total for the carry falls out of the scan.
-// The weights feed the second MFMA (O += A V) straight from registers: the
-// accumulator's per-lane key order is also a valid K-dimension order for the
-// A operand, and V is read from LDS with the transposing load
-// (ds_read_b64_tr_b16) in that same key order.
+// wave's 32 query rows.  In the accumulator a lane owns ONE query column
+// (lane % 32) and 16 key rows; the LDS row fed to MFMA row rho is perm_row(rho),
+// which makes those 16 keys consecutive (lanes 0-31: keys 0..15 of the subtile,
+// lanes 32-63: keys 16..31).  The right-to-left cumulative sum of softplus is
+// then a serial add inside the lane plus one exchange with the partner lane, and
+// the row total for the carry falls out of the scan.  The weights feed the
+// second MFMA (O += A V) straight from registers: the accumulator's per-lane key
+// order is a valid K-dimension order for the A operand, and V is read from LDS
+// with the transposing load in that same key order.
+//
+// Software pipeline.  Step t of a wave runs, in one straight-line block,
+//     MFMA : O += A(t-1) V(t-1)   and   S(t+1) = K(t+1) Q^T
+//     VALU : A(t) from S(t)       (softplus, scan, exp2, bf16 convert)
+// so the matrix pipe works on the neighbours of the subtile whose element-wise
+// path is on the vector pipe; the instruction streams are interleaved with
+// scheduling barriers.  K and V subtiles are brought in by direct global->LDS
+// loads into four-slot rings (subtile j lives in slot j&3), two steps ahead of
+// their use: step t issues the loads of K(t+3) and V(t+1) and, before its closing
+// barrier, waits only for the loads issued in step t-1 (K(t+2), V(t)), so a load
+// has two full steps to land.
 //
 // Arithmetic.  Everything between the two MFMAs is fp32 in the base-2 domain:
-// x = z*log2(e), sp2(x) = log2(1 + 2^x) (v_exp_f32 / v_log_f32 are base 2),
-// A = 2^(x - cumsum sp2 - carry).  log(1-sigma(z)) = -softplus(z) and
-// log(sigma(z)) = z - softplus(z), so no product of probabilities is ever
-// formed.  Where 2^x overflows fp32 (x > 128) softplus is x itself; see sp2().
+// x = z*log2(e), sp2(x) = log2(1 + 2^x), A = 2^(x - cumsum sp2 - carry); see
+// sb_mma.h.  No product of probabilities is formed.
+#include <cstdlib>
+#include <type_traits>
+
 #include "sb_kernels.h"
+#include "sb_mma.h"
 
 namespace sb {
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-
-#define SB_LDS(T, p) ((__attribute__((address_space(3))) T*)(p))
-
-constexpr int BQ = 128;          // query rows per workgroup
-constexpr int BK = 64;           // key rows per LDS tile
 constexpr int NTHREADS = 256;
-constexpr float LOG2E = 1.4426950408889634f;
-constexpr float LN2 = 0.6931471805599453f;
 
 template <int D> struct FwdCfg {
-    static constexpr int KROW = D * 2;          // bytes per K row in LDS (xor-swizzled 16 B chunks)
-    static constexpr int VROW = D * 2 + 64;     // bytes per V row in LDS (padded: rows 16 banks apart)
-    static constexpr int KTILE = BK * KROW;
-    static constexpr int VTILE = BK * VROW;
-    static constexpr int STAGE = KTILE + VTILE; // one buffer
-    static constexpr int LDS_BYTES = 2 * STAGE;
-    static constexpr int CHUNKS_PER_ROW = D / 8;                 // 16 B chunks
-    static constexpr int CHUNKS_PER_THREAD = BK * CHUNKS_PER_ROW / NTHREADS;
+    static constexpr int ROW = D * 2;                   // bytes per tile row (unpadded, swizzled)
+    static constexpr int SUB = 32 * ROW;                // one 32-row subtile
+    static constexpr int NSLOT = 4;                     // ring depth (subtile j in slot j & 3)
+    static constexpr int K_OFF = 0;
+    static constexpr int V_OFF = NSLOT * SUB;
+    static constexpr int LDS_BYTES = 2 * NSLOT * SUB;
+    static constexpr int CPR = ROW / 16;                // 16 B chunks per row
+    static constexpr int BLK_ROWS = 1024 / ROW;         // rows written by one wave-wide 16 B/lane load
+    static constexpr int NI = SUB / 1024 / 4;           // such loads per wave per subtile
 };
 
-// xor mask for the 16 B chunk index of K row `key`: makes the 16 rows that one
-// quarter-wave reads (keys {0..7} and {16..23} (+8) of a subtile) hit 16
-// different 4-bank groups.
-template <int D> __device__ __forceinline__ int k_swizzle(int key)
-{
-    if (D == 128) return (key & 7) | (((key >> 4) & 1) << 3);
-    return ((key >> 1) & 3) | (((key >> 4) & 1) << 2);
-}
+template <bool B> using bc = std::integral_constant<bool, B>;
+template <int I> using ic = std::integral_constant<int, I>;
 
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
-
-// log2(1 + 2^x).  For x > 128 the power overflows to +inf and so does the log;
-// the true value is then x itself to fp32 precision, and the median of
-// (log, x, 128) picks it.  Below that the log lies between x and 128 and wins.
-__device__ __forceinline__ float sp2(float x)
-{
-    return __builtin_amdgcn_fmed3f(fast_log2(1.0f + fast_exp2(x)), x, 128.0f);
-}
-
-template <int D, bool WRITE_M>
-__global__ void __launch_bounds__(NTHREADS, 2)
+template <int D, int NG, bool WRITE_M>
+__global__ void __launch_bounds__(NTHREADS, NG == 1 ? 2 : 1)
 fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                 const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ m,
                 int T, int BH, int nqb)
 {
     using C = FwdCfg<D>;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int BQ = 128 * NG;                        // query rows per workgroup
+    constexpr int WQ = 32 * NG;                         // query rows per wave
+    __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
 
     // workgroup -> (head, query block).  Consecutive workgroup ids go round the 8
     // XCDs, so give every XCD its own heads (K/V of a head stay in one L2) and
@@ -96,185 +84,279 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int n = lane & 31;          // query column inside the wave / MFMA row index
-    const int hh = lane >> 5;         // which half of the wave
-    const int q0 = qb * BQ + wave * 32;
+    const int n = lane & 31;          // query column inside the wave
+    const int hh = lane >> 5;         // half-wave: keys 16*hh .. 16*hh+15 of a subtile
+    const int gg = lane >> 4, li = lane & 15;
+    const int q0 = qb * BQ + wave * WQ;
     const bool wave_live = q0 < T;
 
     const uint16_t* Qg = q + bh * (long)T * D;
     const uint16_t* Kg = k + bh * (long)T * D;
     const uint16_t* Vg = v + bh * (long)T * D;
 
-    // ---- B operand of S^T = K Q^T: Q[q0+n][16s + 8hh .. +7], s = 0..D/16-1
-    bf16x8 qf[D / 16];
-    {
-        const int jq = min(q0 + n, T - 1);
+    // ---- B operand of S^T = K Q^T: Q[q0 + 32g + n][16s + 8hh .. +7], s = 0..D/16-1
+    bf16x8 qf[NG][D / 16];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const int jq = min(q0 + 32 * g + n, T - 1);
         const u32x4* src = reinterpret_cast<const u32x4*>(Qg + (long)jq * D + 8 * hh);
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-            u32x4 w = src[2 * s];
-            qf[s] = __builtin_bit_cast(bf16x8, w);
-        }
+        for (int s = 0; s < D / 16; ++s) qf[g][s] = __builtin_bit_cast(bf16x8, src[2 * s]);
+    }
+    // Make the compiler wait for the Q loads here, once: the staging loads below are
+    // issued behind its back, and a wait for "all my loads" placed inside the loop
+    // would also wait for those.
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) asm volatile("" :: "v"(qf[g][s]));
+
+    // ---- per-lane LDS byte offsets inside a subtile
+    int aoff[D / 16];                       // K rows as A operand: row perm_row(n), chunk 2s + hh
+    {
+        const int key_l = perm_row(n);
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) aoff[s] = tile_off_perm<D>(key_l, 2 * s + hh);
+    }
+    int vtr[D / 32][2];                     // V through the transposing load: rows 16g + li/4 (+4t, +8s)
+    {
+        const int row_l = 16 * (gg >> 1) + (li >> 2);
+        const int cl = 2 * (gg & 1) + ((li & 3) >> 1);
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+                vtr[b][t] = tile_off_perm<D>(row_l + 4 * t, 4 * b + cl) + 8 * (li & 1);
     }
 
-    // ---- per-lane LDS byte offsets
-    // K (A operand): MFMA row rho = n must carry key 16*((rho>>2)&1) + 4*(rho>>3) + (rho&3)
-    const int key_l = 16 * ((n >> 2) & 1) + 4 * (n >> 3) + (n & 3);
-    int koff[D / 16];
+    // ---- direct global -> LDS staging of one 32-row subtile of K or V.
+    // One instruction moves 16 B per lane to 1 KB of consecutive LDS; the swizzle is
+    // applied on the global side: the lane whose LDS position is (row, physical chunk)
+    // fetches the logical chunk that belongs there.  The per-lane byte offset inside
+    // the subtile never changes, so the loop only moves a scalar base address.
+    int goff[C::NI];
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s)
-        koff[s] = key_l * C::KROW + (((2 * s + hh) ^ k_swizzle<D>(key_l)) << 4);
-    // V (B operand through the transposing load): quarter-wave gg = lane/16 reads
-    // rows 16*(gg>>1) + (i>>2), columns 16*(gg&1) + 4*(i&3), i = lane%16
-    const int gg = lane >> 4, li = lane & 15;
-    const int voff = (16 * (gg >> 1) + (li >> 2)) * C::VROW + (16 * (gg & 1) + 4 * (li & 3)) * 2;
-
-    // ---- staging map: thread -> CHUNKS_PER_THREAD 16 B chunks of the K tile and of the V tile
-    u32x4 kst[C::CHUNKS_PER_THREAD], vst[C::CHUNKS_PER_THREAD];
-    auto stage_load = [&](int kt) {
+    for (int i = 0; i < C::NI; ++i) {
+        const int row = (wave * C::NI + i) * C::BLK_ROWS + lane / C::CPR;
+        goff[i] = (row * D + (((lane % C::CPR) ^ swz_perm<D>(row)) << 3)) * 2;
+    }
+    const int top_sub = (min(T, qb * BQ + BQ) - 1 + 31) / 32 - 1;   // topmost staged subtile (may be ragged)
+    auto stage = [&](const uint16_t* g, int sidx, char* slot_ptr) __attribute__((always_inline)) {
+        if (sidx != top_sub) {                      // all 32 rows exist
+            const uint16_t* base = g + (long)sidx * 32 * D;
 #pragma unroll
-        for (int i = 0; i < C::CHUNKS_PER_THREAD; ++i) {
-            const int id = tid + i * NTHREADS;
-            const int row = id / C::CHUNKS_PER_ROW, c = id % C::CHUNKS_PER_ROW;
-            const long gr = min(kt * BK + row, T - 1);
-            kst[i] = *reinterpret_cast<const u32x4*>(Kg + gr * D + c * 8);
-            vst[i] = *reinterpret_cast<const u32x4*>(Vg + gr * D + c * 8);
-        }
-    };
-    auto stage_store = [&](int buf) {
-        char* kb = smem + buf * C::STAGE;
-        char* vb = kb + C::KTILE;
+            for (int i = 0; i < C::NI; ++i)
+                dma16_to_lds_saddr(base, goff[i], slot_ptr + (wave * C::NI + i) * 1024);
+        } else {                                    // rows past T are clamped (they are masked by causality)
 #pragma unroll
-        for (int i = 0; i < C::CHUNKS_PER_THREAD; ++i) {
-            const int id = tid + i * NTHREADS;
-            const int row = id / C::CHUNKS_PER_ROW, c = id % C::CHUNKS_PER_ROW;
-            *reinterpret_cast<u32x4*>(kb + row * C::KROW + ((c ^ k_swizzle<D>(row)) << 4)) = kst[i];
-            *reinterpret_cast<u32x4*>(vb + row * C::VROW + (c << 4)) = vst[i];
+            for (int i = 0; i < C::NI; ++i) {
+                const int row = (wave * C::NI + i) * C::BLK_ROWS + lane / C::CPR;
+                const int c = (lane % C::CPR) ^ swz_perm<D>(row);
+                const long gr = min(sidx * 32 + row, T - 1);
+                dma16_to_lds(g + gr * D + c * 8, slot_ptr + (wave * C::NI + i) * 1024);
+            }
         }
     };
 
-    f32x16 oacc[D / 32];
+    f32x16 oacc[NG][D / 32];
 #pragma unroll
-    for (int b = 0; b < D / 32; ++b)
+    for (int g = 0; g < NG; ++g)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[b][r] = 0.0f;
-    float a = 0.0f;   // carried sum of sp2 over all keys right of the current subtile (this lane's query)
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[g][b][r] = 0.0f;
+    // pipeline registers: sbuf[0] = logits of subtile t, sbuf[1] = of subtile t+1;
+    // pbuf[0] = weights of subtile t-1, pbuf[1] = of subtile t (as MFMA operands).
+    // A step with static phase and odd parity uses them with the roles swapped.
+    f32x16 sbuf[2][NG];
+    bf16x8 pbuf[2][NG][2];
+    float a[NG];                     // carried sum of sp2 over all keys right of the current subtile
+#pragma unroll
+    for (int g = 0; g < NG; ++g) a[g] = 0.0f;
 
-    const float c2 = LOG2E / sqrtf((float)D);
+    const float c2 = SB_LOG2E / sqrtf((float)D);
 
-    // one 32-key subtile: logits, weights, accumulate
-    auto subtile = [&](const char* kb, const char* vb, int u, bool diag) {
-        f32x16 acc;
+    // Element-wise path of one 32x32 subtile of group g: logits sin -> weights pout,
+    // carry a_g updated.  Returns this lane's sum of sp2 (+inf / NaN if a 2^x overflowed
+    // with SAFE = false).  With MASK, key 16hh + r is visible iff 16hh + r < lim.
+    auto ew_group = [&](auto mask_c, auto safe_c, const f32x16& sin, bf16x8 (&pout)[2], float& a_g, int lim) __attribute__((always_inline)) {
+        constexpr bool MASK = decltype(mask_c)::value, SAFE = decltype(safe_c)::value;
+        float y[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+        for (int r = 0; r < 16; ++r) y[r] = sin[r] * c2;
+        if constexpr (MASK) {
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-            const u32x4 w = *reinterpret_cast<const u32x4*>(kb + u * 32 * C::KROW + koff[s]);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), qf[s], acc, 0, 0, 0);
-        }
-        // acc[r] <-> key (tile base) + 32u + 16hh + r, query q0 + n
-        float x[16], cs[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) x[r] = acc[r] * c2;
-        if (diag) {
-            // same 32-row block on both axes: key index 16hh + r is valid iff < n
-#pragma unroll
-            for (int r = 0; r < 16; ++r) x[r] = (16 * hh + r < n) ? x[r] : -INFINITY;
+            for (int r = 0; r < 16; ++r) y[r] = (16 * hh + r < lim) ? y[r] : -INFINITY;
         }
         float run = 0.0f;
 #pragma unroll
         for (int r = 15; r >= 0; --r) {
-            run += sp2(x[r]);
-            cs[r] = run;                       // sum over this lane's keys r..15
+            run += SAFE ? sp2(y[r]) : sp2_fast(y[r]);
+            y[r] -= run;                           // x - (sum of sp2 over this lane's keys r..15)
         }
-        // totals of both half-waves for this query: lanes < 32 get (own, partner), lanes >= 32 (partner, own)
-        auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(int, run), __builtin_bit_cast(int, run), false, false);
-        const float tot_lo = __builtin_bit_cast(float, (int)sw[0]);
-        const float tot_hi = __builtin_bit_cast(float, (int)sw[1]);
-        const float off = a + (hh == 0 ? tot_hi : 0.0f);
-        a += tot_lo + tot_hi;
-        bf16x8 pa[2];
+        float tot_lo, tot_hi;
+        both_halves(run, tot_lo, tot_hi);
+        const float off = a_g + (hh == 0 ? tot_hi : 0.0f);
+        a_g += tot_lo + tot_hi;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float w = fast_exp2((x[r] - off) - cs[r]);
-            pa[r >> 3][r & 7] = (__bf16)w;
+        for (int r = 0; r < 16; ++r) pout[r >> 3][r & 7] = (__bf16)fast_exp2(y[r] - off);
+        return run;
+    };
+
+    // One pipeline step.  HAS_S: form S(t+1); HAS_PV: accumulate A(t-1) V(t-1);
+    // HAS_EW: turn S(t) into A(t).  With MASK, key 16hh + r of the subtile is
+    // visible to the lane's query of group g iff 16hh + r < lim0 + 32g.
+    // PHASE = (t+1)&3 fixes the ring slots (and register roles) at compile time;
+    // PHASE = -1 takes them from t and rotates the pipeline registers at the end.
+    auto step = [&](auto has_pv, auto has_ew, auto has_s, auto mask, auto phase_c, int t, int lim0) __attribute__((always_inline)) {
+        constexpr bool HAS_PV = decltype(has_pv)::value, HAS_EW = decltype(has_ew)::value;
+        constexpr bool HAS_S = decltype(has_s)::value, MASK = decltype(mask)::value;
+        constexpr int PHASE = decltype(phase_c)::value;
+        constexpr int Q = PHASE < 0 ? 0 : (PHASE & 1);              // register parity
+        const char* kslot = smem + C::K_OFF + (PHASE < 0 ? ((t + 1) & 3) : PHASE) * C::SUB;        // K(t+1)
+        const char* vslot = smem + C::V_OFF + (PHASE < 0 ? ((t - 1) & 3) : ((PHASE + 2) & 3)) * C::SUB;   // V(t-1)
+        f32x16 (&s_in)[NG] = sbuf[Q];
+        f32x16 (&s_out)[NG] = sbuf[Q ^ 1];
+        bf16x8 (&p_in)[NG][2] = pbuf[Q];
+        bf16x8 (&p_out)[NG][2] = pbuf[Q ^ 1];
+
+        if constexpr (HAS_S) {
+            f32x16 acc[NG];
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[g][r] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+                const u32x4 w = *reinterpret_cast<const u32x4*>(kslot + aoff[s]);
+#pragma unroll
+                for (int g = 0; g < NG; ++g)
+                    acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), qf[g][s], acc[g], 0, 0, 0);
+            }
+#pragma unroll
+            for (int g = 0; g < NG; ++g) s_out[g] = acc[g];
         }
-        // O[q][dcol] += sum_keys A[q][key] V[key][dcol]; K-dim index 8g+e <-> key 16g + 8s + e
+        if constexpr (HAS_PV) {
+            // O[q][dcol] += sum_keys A[q][key] V[key][dcol]; K-dim index 8h+e <-> key 16h + 8s + e
 #pragma unroll
-        for (int b = 0; b < D / 32; ++b) {
+            for (int b = 0; b < D / 32; ++b) {
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                const char* vp = vb + (u * 32 + 8 * s) * C::VROW + b * 64 + voff;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SB_LDS(s16x4, vp));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SB_LDS(s16x4, vp + 4 * C::VROW));
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[s], vf, oacc[b], 0, 0, 0);
+                for (int s = 0; s < 2; ++s) {
+                    const char* p = vslot + (8 * s) * C::ROW;
+                    const bf16x8 vf = tr_pair(p + vtr[b][0], p + vtr[b][1]);
+#pragma unroll
+                    for (int g = 0; g < NG; ++g)
+                        oacc[g][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p_in[g][s], vf, oacc[g][b], 0, 0, 0);
+                }
+            }
+        }
+        if constexpr (HAS_EW) {
+#pragma unroll
+            for (int g = 0; g < NG; ++g) ew_group(bc<MASK>{}, bc<true>{}, s_in[g], p_out[g], a[g], lim0 + 32 * g);
+            if constexpr (HAS_PV || HAS_S) {
+                // interleave: one MFMA, then a slice of the element-wise stream
+                constexpr int NMFMA = NG * ((HAS_PV ? D / 16 : 0) + (HAS_S ? D / 16 : 0));
+                constexpr int SLICE = (130 * NG) / NMFMA;
+#pragma unroll
+                for (int i = 0; i < NMFMA; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x402, SLICE, 0);   // VALU incl. transcendental
+                }
+            }
+        }
+        if constexpr (PHASE < 0) {
+            // rotate the pipeline registers
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                if constexpr (HAS_S) sbuf[0][g] = sbuf[1][g];
+                if constexpr (HAS_EW) { pbuf[0][g][0] = pbuf[1][g][0]; pbuf[0][g][1] = pbuf[1][g][1]; }
             }
         }
     };
 
-    // ---- sweep over key tiles, right to left
+    // ---- the sweep
     const int jmax = min(T, qb * BQ + BQ) - 1;          // last live query row of the workgroup
-    const int ntile = (jmax + BK - 1) / BK;              // tiles covering keys 0 .. jmax-1
-    if (ntile > 0) {
-        stage_load(ntile - 1);
-        stage_store(0);
-    }
-    __syncthreads();
-    for (int it = 0; it < ntile; ++it) {
-        const int kt = ntile - 1 - it;
-        const int buf = it & 1;
-        const char* kb = smem + buf * C::STAGE;
-        const char* vb = kb + C::KTILE;
-        const bool more = it + 1 < ntile;
-        if (more) stage_load(kt - 1);
-        {
-            const int k0 = kt * BK + 32;
-            if (wave_live && k0 <= q0) subtile(kb, vb, 1, k0 == q0);
-        }
-        if (more) stage_store(buf ^ 1);
-        {
-            const int k0 = kt * BK;
-            if (wave_live && k0 <= q0) subtile(kb, vb, 0, k0 == q0);
-        }
-        __syncthreads();
-    }
+    const int nsub = (jmax + 31) >> 5;                   // subtiles covering keys 0 .. jmax-1
+    // this wave's subtiles: from the diagonal of its last group (or the last staged one) down to 0
+    const int nw = wave_live ? min((q0 >> 5) + NG, nsub) : 0;
+    const int t0w = nsub - nw;                           // global step of the wave's first subtile
+    // from this step on every live wave is past its diagonals (wave 0 is the last to get there)
+    const int t_clean = nsub - min(((qb * BQ) >> 5) + NG, nsub) + NG;
 
-    // ---- store.  oacc[b][r] is query row 8*(r/4) + 4*hh + r%4, column 32b + n.
+    // subtile handled at step j is number nsub-1-j (counted from key 0); past the end re-load
+    // subtile 0 into a slot nobody reads, which keeps the number of loads per step constant
+    auto stage_step = [&](int t) __attribute__((always_inline)) {
+        stage(Kg, max(nsub - 1 - (t + 3), 0), smem + C::K_OFF + ((t + 3) & 3) * C::SUB);
+        stage(Vg, max(nsub - 1 - (t + 1), 0), smem + C::V_OFF + ((t + 1) & 3) * C::SUB);
+    };
+    auto end_step = [&]() __attribute__((always_inline)) {
+        dma_wait<2 * C::NI>();       // everything but this step's own 2*NI loads has landed
+        barrier_nofence();
+    };
+    // a step whose variant depends on where this wave is in its own pipeline
+    auto generic_step = [&](int t) __attribute__((always_inline)) {
+        stage_step(t);
+        const int tau = t - t0w;                         // the wave's own step index
+        if (nw > 0 && tau >= -1) {
+            // key 32*sidx + 16hh + r is visible to query q0 + 32g + n iff it is smaller
+            const int lim0 = q0 + n - 32 * (nsub - 1 - t);
+            if (tau == -1) step(bc<false>{}, bc<false>{}, bc<true>{}, bc<false>{}, ic<-1>{}, t, 0);
+            else if (tau == 0) step(bc<false>{}, bc<true>{}, bc<true>{}, bc<true>{}, ic<-1>{}, t, lim0);
+            else if (tau < NG) step(bc<true>{}, bc<true>{}, bc<true>{}, bc<true>{}, ic<-1>{}, t, lim0);
+            else step(bc<true>{}, bc<true>{}, bc<true>{}, bc<false>{}, ic<-1>{}, t, 0);
+        }
+        end_step();
+    };
+    if (nsub > 0) {
+        stage(Kg, max(nsub - 1, 0), smem + C::K_OFF);                  // K(0)
+        stage(Kg, max(nsub - 2, 0), smem + C::K_OFF + C::SUB);         // K(1)
+    }
+    dma_wait<0>();
+    barrier_nofence();
+
+    int t = -1;
+    // ramp: waves enter their pipelines one after the other and pass their diagonals
+    for (; t < min(t_clean, nsub); ++t) generic_step(t);
+    // steady state: every live wave runs the full step
+    for (; t < nsub; ++t) {                              // the last step forms an S that is never used
+        stage_step(t);
+        if (nw > 0) step(bc<true>{}, bc<true>{}, bc<true>{}, bc<false>{}, ic<-1>{}, t, 0);
+        end_step();
+    }
+    if (nw > 0) step(bc<true>{}, bc<false>{}, bc<false>{}, bc<false>{}, ic<-1>{}, t, 0);   // drain: O += A(last) V(last)
+    dma_wait<0>();                                       // the trailing re-loads
+
+    // ---- store.  oacc[g][b][r] is query row 32g + 8*(r/4) + 4*hh + r%4, column 32b + n.
     if (wave_live) {
         uint16_t* Og = o + bh * (long)T * D;
+        const bool full = q0 + WQ <= T;
 #pragma unroll
-        for (int b = 0; b < D / 32; ++b) {
+        for (int g = 0; g < NG; ++g) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = q0 + 8 * (r >> 2) + 4 * hh + (r & 3);
-                if (row < T) {
-                    const __bf16 val = (__bf16)oacc[b][r];
-                    Og[(long)row * D + 32 * b + n] = __builtin_bit_cast(uint16_t, val);
+            for (int b = 0; b < D / 32; ++b) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = q0 + 32 * g + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    if (full || row < T) {
+                        const __bf16 val = (__bf16)oacc[g][b][r];
+                        Og[(long)row * D + 32 * b + n] = __builtin_bit_cast(uint16_t, val);
+                    }
                 }
             }
+            if (WRITE_M && hh == 0 && q0 + 32 * g + n < T) m[bh * (long)T + q0 + 32 * g + n] = -a[g] * SB_LN2;
         }
-        if (WRITE_M && hh == 0 && q0 + n < T) m[bh * (long)T + q0 + n] = -a * LN2;
     }
 }
 
-template <int D, bool WRITE_M>
+template <int D, int NG, bool WRITE_M>
 hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o, float* m,
                       int BH, int T, hipStream_t stream)
 {
-    using C = FwdCfg<D>;
-    auto kern = fwd_bf16_kernel<D, WRITE_M>;
-    static bool attr_done = false;   // the attribute is per function, set once per process
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    constexpr int BQ = 128 * NG;
     const int nqb = (T + BQ - 1) / BQ;
     const long blocks = 8L * ((BH + 7) / 8) * nqb;
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), C::LDS_BYTES, stream,
+    hipLaunchKernelGGL((fwd_bf16_kernel<D, NG, WRITE_M>), dim3((unsigned)blocks), dim3(NTHREADS), 0, stream,
                        q, k, v, o, m, T, BH, nqb);
     return hipGetLastError();
 }
@@ -286,10 +368,14 @@ hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t*
 {
     const int BH = B * H;
     if (d == 64)
-        return m ? launch_one<64, true>(q, k, v, o, m, BH, T, stream)
-                 : launch_one<64, false>(q, k, v, o, m, BH, T, stream);
-    return m ? launch_one<128, true>(q, k, v, o, m, BH, T, stream)
-             : launch_one<128, false>(q, k, v, o, m, BH, T, stream);
+        return m ? launch_one<64, 1, true>(q, k, v, o, m, BH, T, stream)
+                 : launch_one<64, 1, false>(q, k, v, o, m, BH, T, stream);
+    static const int ng = getenv("SB_FWD_NG") ? atoi(getenv("SB_FWD_NG")) : 1;   // tuning knob (temporary)
+    if (ng == 1)
+        return m ? launch_one<128, 1, true>(q, k, v, o, m, BH, T, stream)
+                 : launch_one<128, 1, false>(q, k, v, o, m, BH, T, stream);
+    return m ? launch_one<128, 2, true>(q, k, v, o, m, BH, T, stream)
+             : launch_one<128, 2, false>(q, k, v, o, m, BH, T, stream);
 }
 
 }  // namespace sb

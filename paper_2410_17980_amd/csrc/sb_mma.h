@@ -55,6 +55,10 @@ template <int D> __device__ __forceinline__ int swz_nat(int row)
     return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
 }
 
+// sp2 without the overflow guard: +inf for x > 128 (the caller checks its sums and
+// falls back to sp2)
+__device__ __forceinline__ float sp2_fast(float x) { return fast_log2(1.0f + fast_exp2(x)); }
+
 // byte offset of 16-byte chunk c of tile row `row`
 template <int D> __device__ __forceinline__ int tile_off_perm(int row, int c)
 {
@@ -82,6 +86,46 @@ __device__ __forceinline__ void both_halves(float v, float& lo, float& hi)
     auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(int, v), __builtin_bit_cast(int, v), false, false);
     lo = __builtin_bit_cast(float, (int)sw[0]);
     hi = __builtin_bit_cast(float, (int)sw[1]);
+}
+
+// Direct global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): lane l
+// of the wave writes LDS bytes [lds_base + 16 l, +16) with the 16 bytes at its own
+// global address; lds_base must be wave-uniform.  Issued through inline assembly so
+// that the compiler's wait-count pass does not see an LDS write it would guard
+// every later LDS read against; the caller orders it with dma_wait<N>() + barrier.
+// Completion is counted in vmcnt, in issue order.
+__device__ __forceinline__ void dma16_to_lds(const void* gptr, const char* lds_base)
+{
+    const uint32_t lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)SB_LDS(const char, lds_base));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds), "v"(gptr) : "memory");
+}
+
+// same, with the global address given as a wave-uniform base plus a per-lane byte offset
+__device__ __forceinline__ void dma16_to_lds_saddr(const void* gbase, int lane_off, const char* lds_base)
+{
+    const uint32_t lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)SB_LDS(const char, lds_base));
+    const uint64_t b = (uint64_t)(uintptr_t)gbase;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    const uint64_t sb = ((uint64_t)hi << 32) | lo;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds), "v"(lane_off), "s"(sb) : "memory");
+}
+
+// wait until at most N of this wave's vector-memory operations are outstanding
+template <int N> __device__ __forceinline__ void dma_wait()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+// workgroup barrier without the compiler's "wait for everything" fence: the caller
+// has already waited for exactly what must be visible
+__device__ __forceinline__ void barrier_nofence()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
 
 }  // namespace sb
