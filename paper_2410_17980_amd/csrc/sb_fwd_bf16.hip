@@ -274,6 +274,148 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         }
     };
 
+    // ---- the steady-state step, scheduled by hand (one query group per wave).
+    // The same work as step(PV, EW, S) above, laid out as 2*D/16 slots: each slot
+    // issues the LDS reads of the MFMA two slots ahead, one MFMA (S and PV products
+    // alternate, so consecutive links of the S accumulation chain are a slot
+    // apart), and one or two chunks of the element-wise stream.  The element-wise
+    // stream is ordered stage by stage over all 16 elements of the lane (scale,
+    // 2^x, +1, log2, guarded scan, shift, 2^x, convert) rather than element by
+    // element, so that no instruction waits on the one just before it; scheduling
+    // barriers keep the compiler from folding it back.
+    auto hot_step = [&](int t) __attribute__((always_inline)) {
+        static_assert(NG == 1 || NG == 2, "");
+        constexpr int NM = D / 16;                 // MFMAs of each product
+        constexpr int NSLOT = 2 * NM;
+        const char* kslot = smem + C::K_OFF + ((t + 1) & 3) * C::SUB;     // K(t+1)
+        const char* vslot = smem + C::V_OFF + ((t - 1) & 3) * C::SUB;     // V(t-1)
+        const f32x16& s_in = sbuf[0][0];
+        bf16x8 (&p_in)[2] = pbuf[0][0];
+        bf16x8 (&p_out)[2] = pbuf[1][0];
+
+        u32x4 kop[NM];
+        bf16x8 vop[NM];
+        auto fetch = [&](auto ic_i) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic_i)::value;
+            if constexpr (i < NSLOT) {
+                if constexpr ((i & 1) == 0) {
+                    kop[i / 2] = *reinterpret_cast<const u32x4*>(kslot + aoff[i / 2]);
+                } else {
+                    constexpr int j = i / 2, b = j / 2, sh = j % 2;
+                    const char* p = vslot + (8 * sh) * C::ROW;
+                    vop[j] = tr_pair(p + vtr[b][0], p + vtr[b][1]);
+                }
+            }
+        };
+        f32x16 acc;
+        float x[16], w[16];
+        float run = 0.0f, off = 0.0f;
+        auto mfma = [&](auto ic_i) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic_i)::value;
+            if constexpr ((i & 1) == 0) {
+                constexpr int sI = i / 2;
+                if constexpr (sI == 0) {
+                    f32x16 z;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) z[r] = 0.0f;
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop[0]), qf[0][0], z, 0, 0, 0);
+                } else {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop[sI]), qf[0][sI], acc, 0, 0, 0);
+                }
+            } else {
+                constexpr int j = i / 2, b = j / 2, sh = j % 2;
+                oacc[0][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p_in[sh], vop[j], oacc[0][b], 0, 0, 0);
+            }
+        };
+        auto chunk = [&](auto ic_c) __attribute__((always_inline)) {
+            constexpr int c = decltype(ic_c)::value;
+            if constexpr (c == 0) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) x[r] = s_in[r] * c2;
+            } else if constexpr (c == 1) {
+#pragma unroll
+                for (int r = 15; r >= 10; --r) w[r] = fast_exp2(x[r]);
+            } else if constexpr (c == 2) {
+#pragma unroll
+                for (int r = 9; r >= 4; --r) w[r] = fast_exp2(x[r]);
+            } else if constexpr (c == 3) {
+#pragma unroll
+                for (int r = 3; r >= 0; --r) w[r] = fast_exp2(x[r]);
+#pragma unroll
+                for (int r = 15; r >= 8; --r) w[r] += 1.0f;
+            } else if constexpr (c == 4) {
+#pragma unroll
+                for (int r = 7; r >= 0; --r) w[r] += 1.0f;
+#pragma unroll
+                for (int r = 15; r >= 13; --r) w[r] = fast_log2(w[r]);
+            } else if constexpr (c == 5) {
+#pragma unroll
+                for (int r = 12; r >= 7; --r) w[r] = fast_log2(w[r]);
+            } else if constexpr (c == 6) {
+#pragma unroll
+                for (int r = 6; r >= 0; --r) w[r] = fast_log2(w[r]);
+            } else if constexpr (c == 7 || c == 8 || c == 9) {
+                constexpr int hi = c == 7 ? 15 : (c == 8 ? 10 : 5), lo = c == 7 ? 11 : (c == 8 ? 6 : 0);
+#pragma unroll
+                for (int r = hi; r >= lo; --r) w[r] = __builtin_amdgcn_fmed3f(w[r], x[r], 128.0f);   // sp2, overflow-proof
+#pragma unroll
+                for (int r = hi; r >= lo; --r) {
+                    run += w[r];
+                    x[r] -= run;                   // x - (sum of sp2 over this lane's keys r..15)
+                }
+            } else if constexpr (c == 10) {
+                float tot_lo, tot_hi;
+                both_halves(run, tot_lo, tot_hi);
+                off = a[0] + (hh == 0 ? tot_hi : 0.0f);
+                a[0] += tot_lo + tot_hi;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) x[r] -= off;
+            } else if constexpr (c == 11) {
+#pragma unroll
+                for (int r = 0; r < 6; ++r) w[r] = fast_exp2(x[r]);
+            } else if constexpr (c == 12) {
+#pragma unroll
+                for (int r = 6; r < 12; ++r) w[r] = fast_exp2(x[r]);
+            } else if constexpr (c == 13) {
+#pragma unroll
+                for (int r = 12; r < 16; ++r) w[r] = fast_exp2(x[r]);
+#pragma unroll
+                for (int r = 0; r < 8; ++r) p_out[0][r] = (__bf16)w[r];
+            } else if constexpr (c == 14) {
+#pragma unroll
+                for (int r = 8; r < 16; ++r) p_out[1][r & 7] = (__bf16)w[r];
+            }
+        };
+
+        fetch(ic<0>{});
+        fetch(ic<1>{});
+        __builtin_amdgcn_sched_barrier(0);
+        auto slot_body = [&](auto ic_i) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic_i)::value;
+            fetch(ic<i + 2>{});
+            mfma(ic<i>{});
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (NSLOT == 16) {
+                chunk(ic<i>{});
+            } else {
+                chunk(ic<2 * i>{});
+                __builtin_amdgcn_sched_barrier(0);
+                chunk(ic<2 * i + 1>{});
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        slot_body(ic<0>{}); slot_body(ic<1>{}); slot_body(ic<2>{}); slot_body(ic<3>{});
+        slot_body(ic<4>{}); slot_body(ic<5>{}); slot_body(ic<6>{}); slot_body(ic<7>{});
+        if constexpr (NSLOT == 16) {
+            slot_body(ic<8>{}); slot_body(ic<9>{}); slot_body(ic<10>{}); slot_body(ic<11>{});
+            slot_body(ic<12>{}); slot_body(ic<13>{}); slot_body(ic<14>{}); slot_body(ic<15>{});
+        }
+        // rotate the pipeline registers
+        sbuf[0][0] = acc;
+        pbuf[0][0][0] = pbuf[1][0][0];
+        pbuf[0][0][1] = pbuf[1][0][1];
+    };
+
     // ---- the sweep
     const int jmax = min(T, qb * BQ + BQ) - 1;          // last live query row of the workgroup
     const int nsub = (jmax + 31) >> 5;                   // subtiles covering keys 0 .. jmax-1
@@ -320,7 +462,10 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     // steady state: every live wave runs the full step
     for (; t < nsub; ++t) {                              // the last step forms an S that is never used
         stage_step(t);
-        if (nw > 0) step(bc<true>{}, bc<true>{}, bc<true>{}, bc<false>{}, ic<-1>{}, t, 0);
+        if (nw > 0) {
+            if constexpr (NG == 1) hot_step(t);
+            else step(bc<true>{}, bc<true>{}, bc<true>{}, bc<false>{}, ic<-1>{}, t, 0);
+        }
         end_step();
     }
     if (nw > 0) step(bc<true>{}, bc<false>{}, bc<false>{}, bc<false>{}, ic<-1>{}, t, 0);   // drain: O += A(last) V(last)
