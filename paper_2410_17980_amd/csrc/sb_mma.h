@@ -55,10 +55,6 @@ template <int D> __device__ __forceinline__ int swz_nat(int row)
     return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
 }
 
-// sp2 without the overflow guard: +inf for x > 128 (the caller checks its sums and
-// falls back to sp2)
-__device__ __forceinline__ float sp2_fast(float x) { return fast_log2(1.0f + fast_exp2(x)); }
-
 // byte offset of 16-byte chunk c of tile row `row`
 template <int D> __device__ __forceinline__ int tile_off_perm(int row, int c)
 {
