@@ -7,25 +7,37 @@
 // query row and per 32-key subtile, the two carried scalars
 //     ca = sum of sp2 over the keys to the right of the subtile (up to the query),
 //     cb = sum of G = A*(dO.v) over the keys to the left of the subtile,
-// (2 floats per 32x1 strip of the attention matrix).  With them any subtile can
-// be recomputed on its own, so dK and dV are accumulated by a key-stationary
-// kernel in registers and written once, with no atomics and no zero fill, and
-// the result is bit-reproducible.
+// (2 floats per 32x1 strip of the attention matrix; sp2 = base-2 softplus).  With
+// them any subtile can be recomputed on its own, so dK and dV are accumulated by a
+// key-stationary kernel in registers and written once, with no atomics and no
+// zero fill, and the result is bit-reproducible.
 //
-//   bwd_dq_kernel  (query-stationary, 128 query rows per workgroup, sweep from
-//                   key 0 to the diagonal as Algorithm 2): recomputes A from m,
-//                   forms G and dZ, accumulates dQ += (dZ/sqrt d) K, stores ca, cb.
-//   bwd_dkv_kernel (key-stationary, 128 key rows per workgroup = 32 per wave,
-//                   K and V rows held in registers, sweep over query blocks from
-//                   the diagonal to the end): recomputes A, G, dZ from ca, cb and
-//                   accumulates dV += A^T dO, dK += (dZ/sqrt d)^T Q.
+//   bwd_dq_kernel  (query-stationary, 128 query rows per block, sweep from key 0
+//                   to the diagonal as Algorithm 2): recomputes A from m, forms G
+//                   and dZ, accumulates dQ += dZ K, stores ca, cb.
+//   bwd_dkv_kernel (key-stationary, 128 key rows per block = 32 per wave, K and V
+//                   rows held in registers, sweep over query tiles from the
+//                   diagonal to the end): recomputes A, G, dZ from ca, cb and
+//                   accumulates dV += A^T dO, dK += dZ^T Q.
+// The element-wise arithmetic runs in the linear domain inside a lane (one exponential
+// and one reciprocal per element, see subtile_stage1/2); where its running product
+// leaves the fp32 range (sharp logits) the kernel only records that in a per-block
+// flag, and a second launch of the same kernel in its log-domain variant (SLOW)
+// redoes exactly the flagged blocks and returns at once for the others.  Keeping the
+// overflow-proof form out of the fast kernels keeps them within their register budget.
+// Both kernels give a workgroup two blocks, p and n-1-p, whose causal costs add up
+// to the same total for every p, and stage their streamed tiles with direct
+// global->LDS loads, double buffered, one barrier per 64-row tile.  The 1/sqrt(d)
+// of dQ and dK is applied once, to the accumulators, on store.
 //
 // Register layout is the forward's: S^T = K Q^T and P^T = V dO^T with the
 // 32x32x16 bf16 MFMA, a lane owns one query column and 16 consecutive keys, so
-// both cumulative sums are serial inside the lane plus one exchange between the
-// half-waves.  A and dZ feed the "query-major" product (dQ) straight from
-// registers; for the "key-major" products (dK, dV) they are written to a small
+// both cumulative quantities are serial inside the lane plus one exchange between
+// the half-waves.  dZ feeds the "query-major" product (dQ) straight from
+// registers; for the "key-major" products (dK, dV) A and dZ are written to a small
 // per-wave LDS scratch row-wise and read back with the transposing load.
+#include <type_traits>
+
 #include "sb_kernels.h"
 #include "sb_mma.h"
 
@@ -33,34 +45,33 @@ namespace sb {
 namespace {
 
 constexpr int NTHREADS = 256;
-constexpr int BQ = 128;      // dq kernel: query rows per workgroup
-constexpr int BK = 64;       // dq kernel: key rows per LDS tile
-constexpr int BKW = 128;     // dkv kernel: key rows per workgroup (32 per wave)
+constexpr int NW = 4;        // wavefronts per workgroup
+constexpr int BQ = 128;      // dq kernel: query rows per block
+constexpr int BKW = 128;     // dkv kernel: key rows per block (32 per wave)
+constexpr int TK = 64;       // rows per staged tile (keys in the dq kernel, queries in the dkv kernel)
 constexpr int TROW = 80;     // scratch row: 32 bf16 + pad (rows stay 16 B aligned)
+
+template <bool B> using bc = std::integral_constant<bool, B>;
 
 // ------------------------------------------------------------------ element-wise core
 // One 32x32 subtile in the lane layout (query n; keys 16hh + r).
 struct SubtileOut {
     bf16x8 pa[2];    // A, as MFMA operand (K-dim element e of half s <-> key 16hh + 8s + e)
-    bf16x8 pz[2];    // dZ / sqrt(d), same layout
+    bf16x8 pz[2];    // dZ (without the 1/sqrt(d)), same layout
     float ca_right;  // sum of sp2 over the keys right of the subtile
     float g_tot;     // sum of G over the subtile's 32 keys
 };
 
-// sacc: q.k accumulator, pacc: dO.v accumulator.  cb: sum of G over the keys left
-// of the subtile.  ca: sum of sp2 over the keys right of the subtile, or, with
-// CA_INCLUDES_SUBTILE, over the subtile's own keys as well (Algorithm 2 carries
-// that and subtracts the subtile's total before use).
-template <bool CA_INCLUDES_SUBTILE>
-__device__ __forceinline__ SubtileOut subtile_math(const f32x16& sacc, const f32x16& pacc, float ca,
-                                                   float cb, float c2, float scale, int n, int hh, bool diag)
+// Log-domain form (Eq. 2 / Eq. 4 as printed), overflow-proof; used only where the
+// linear-domain chain of subtile_math leaves its range.
+template <bool CA_INCLUDES_SUBTILE, bool MASK>
+__device__ __forceinline__ void subtile_math_log(SubtileOut& out, const f32x16& sacc, const f32x16& pacc,
+                                              float ca, float cb, float c2, int n, int hh)
 {
-    SubtileOut out;
     float x[16], sp[16], cs[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) x[r] = sacc[r] * c2;
-    if (diag) {
-        // same 32 rows on both axes: key 16hh + r is visible to query n iff it is smaller
+    if (MASK) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) x[r] = (16 * hh + r < n) ? x[r] : -INFINITY;
     }
@@ -94,68 +105,154 @@ __device__ __forceinline__ SubtileOut subtile_math(const f32x16& sacc, const f32
     for (int r = 0; r < 16; ++r) {
         const float beta = fast_exp2(x[r] - sp[r]);        // sigma(z)
         const float dz = g[r] - beta * (pre[r] + boff);    // Eq. 4
-        out.pz[r >> 3][r & 7] = (__bf16)(dz * scale);
+        out.pz[r >> 3][r & 7] = (__bf16)dz;
     }
-    return out;
+}
+
+// The same in the linear domain inside the lane, as in the forward: with e_r = 2^{x_r}
+// the chain t_r = W_r e_r, W_{r+1} = W_r + t_r over ascending keys gives
+// A[r] = t_r / W_16 * 2^-(sp2 total of all nearer keys), and sigma = e / (1 + e):
+// one exponential and one reciprocal per element instead of three exponentials and
+// a logarithm.  W_0 = 2^-60; a chain that gets beyond 2^80 (or overflows) makes the
+// caller redo the subtile with subtile_math_log.  Two stages, so that the dO.v
+// accumulator need not be live during the first:
+//   stage 1 (logits only): sigma, chain.  Returns false in a lane whose chain left its range.
+//   stage 2 (needs dO.v): A, G, dZ.
+// sacc: q.k accumulator, pacc: dO.v accumulator.  cb: sum of G over the keys left
+// of the subtile.  ca: sum of sp2 over the keys right of the subtile, or, with
+// CA_INCLUDES_SUBTILE, over the subtile's own keys as well (Algorithm 2 carries
+// that and subtracts the subtile's total before use).  With MASK, key 16hh + r is
+// visible to query n iff 16hh + r < n (the subtile on the diagonal).
+struct Chain {
+    float be[16];    // sigma(z)
+    float t[16];     // chain terms, later G
+    float W;         // end of the chain
+};
+
+template <bool MASK>
+__device__ __forceinline__ bool subtile_stage1(Chain& ch, const f32x16& sacc, float c2, int n, int hh)
+{
+    float W = 0x1p-60f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        float e = fast_exp2(sacc[r] * c2);
+        if (MASK) e = (16 * hh + r < n) ? e : 0.0f;
+        ch.t[r] = W * e;
+        W += ch.t[r];
+        ch.be[r] = e * __builtin_amdgcn_rcpf(1.0f + e);
+    }
+    ch.W = W;
+    return W < 0x1p80f;                                    // false: this lane's chain left its range
+}
+
+template <bool CA_INCLUDES_SUBTILE, bool NEED_A>
+__device__ __forceinline__ void subtile_stage2(SubtileOut& out, Chain& ch, const f32x16& pacc,
+                                               float ca, float cb, int hh)
+{
+    const float l = fast_log2(ch.W) + 60.0f;               // sp2 total of this lane's 16 keys
+    float l_lo, l_hi;
+    both_halves(l, l_lo, l_hi);
+    const float car = CA_INCLUDES_SUBTILE ? ca - (l_lo + l_hi) : ca;
+    out.ca_right = car;
+    // keys 16..31 (hh = 1) are nearer to the query than keys 0..15
+    const float kf = fast_exp2(60.0f - (car + l_hi + (hh == 0 ? l_lo : 0.0f)));
+    // dZ = G - sigma * (prefix of G + boff), boff = cb + the partner half's total for the
+    // nearer half: the part that needs boff is added once boff is known
+    float grun = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float w = ch.t[r] * kf;                      // A
+        if (NEED_A) out.pa[r >> 3][r & 7] = (__bf16)w;
+        const float g = w * pacc[r];                       // G = dL/dlogA = A * dL/dA
+        grun += g;                                         // inclusive prefix inside the lane
+        ch.t[r] = g - ch.be[r] * grun;
+    }
+    float g_lo, g_hi;
+    both_halves(grun, g_lo, g_hi);
+    out.g_tot = g_lo + g_hi;
+    const float boff = cb + (hh == 1 ? g_lo : 0.0f);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float dz = ch.t[r] - ch.be[r] * boff;        // Eq. 4
+        out.pz[r >> 3][r & 7] = (__bf16)dz;
+    }
+}
+
+// ------------------------------------------------------------------ staging
+// Direct global -> LDS staging of 64-row tiles of two [T][D] matrices (X then Y in
+// one stage).  One instruction moves 16 B per lane to 1 KB of consecutive LDS; the
+// swizzle is applied on the global side.  PERM selects the swizzle (see sb_mma.h).
+template <int D> struct StageCfg {
+    static constexpr int ROW = D * 2;
+    static constexpr int TILE = TK * ROW;               // one 64-row tile
+    static constexpr int STAGE = 2 * TILE;
+    static constexpr int CPR = ROW / 16;
+    static constexpr int BLK_ROWS = 1024 / ROW;
+    static constexpr int NPW = TILE / 1024 / NW;        // loads per wave per tile
+};
+
+template <int D, bool PERM>
+__device__ __forceinline__ void stage_tile(const uint16_t* X, const uint16_t* Y, int jt, int T, char* sp,
+                                           int wave, int lane)
+{
+    using C = StageCfg<D>;
+    const bool full = (jt + 1) * TK <= T;
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const uint16_t* G = m == 0 ? X : Y;
+        char* base = sp + m * C::TILE;
+#pragma unroll
+        for (int i = 0; i < C::NPW; ++i) {
+            const int row = (wave * C::NPW + i) * C::BLK_ROWS + lane / C::CPR;
+            const int swz = PERM ? swz_perm<D>(row) : swz_nat<D>(row);
+            const int c = (lane % C::CPR) ^ swz;
+            if (full) {
+                dma16_to_lds_saddr(G + (long)jt * TK * D, (row * D + c * 8) * 2, base + (wave * C::NPW + i) * 1024);
+            } else {                                    // rows past T are clamped (their results are masked)
+                const long gr = min(jt * TK + row, T - 1);
+                dma16_to_lds(G + gr * D + c * 8, base + (wave * C::NPW + i) * 1024);
+            }
+        }
+    }
 }
 
 // ------------------------------------------------------------------ dQ kernel
-template <int D> struct DqCfg {
-    static constexpr int ROW = D * 2;
-    static constexpr int TILE = BK * ROW;
-    static constexpr int STAGE = 2 * TILE;           // K tile + V tile
-    static constexpr int LDS_BYTES = 2 * STAGE;      // double buffered
-    static constexpr int CPR = D / 8;                // 16 B chunks per row
-    static constexpr int CPT = BK * CPR / NTHREADS;  // chunks per thread per tile
-};
-
-template <int D>
-__global__ void __launch_bounds__(NTHREADS, 2)
+template <int D, bool SLOW>
+__global__ void __launch_bounds__(NTHREADS, SLOW ? 1 : 2)
 bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
               const uint16_t* __restrict__ v, const float* __restrict__ m,
               const uint16_t* __restrict__ dout, float* __restrict__ dq,
-              float* __restrict__ ca, float* __restrict__ cb, int T, int BH, int nqb, int nt32)
+              float* __restrict__ ca, float* __restrict__ cb, int* __restrict__ flags,
+              int T, int BH, int nqb, int nt32)
 {
-    using C = DqCfg<D>;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    using C = StageCfg<D>;
+    __shared__ __attribute__((aligned(1024))) char smem[2 * C::STAGE];
+    __shared__ int s_dirty;
 
     const int wg = blockIdx.x;
     const int xcd = wg & 7, slot = wg >> 3;
-    const long bh = xcd + 8L * (slot / nqb);
-    const int qb = nqb - 1 - (slot % nqb);
+    const int npair = (nqb + 1) >> 1;
+    const long bh = xcd + 8L * (slot / npair);
+    const int pidx = slot % npair;
     if (bh >= BH) return;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, hh = lane >> 5;
     const int gg = lane >> 4, li = lane & 15;
-    const int q0 = qb * BQ + wave * 32;
-    const bool wave_live = q0 < T;
-    const int jq = min(q0 + n, T - 1);
 
     const long base = bh * (long)T * D;
     const uint16_t* Kg = k + base;
     const uint16_t* Vg = v + base;
 
-    // B operands: this lane's query row of Q and dO (dO = 0 past T: such rows contribute nothing)
-    bf16x8 qf[D / 16], gf[D / 16];
-    {
-        const u32x4* qs = reinterpret_cast<const u32x4*>(q + base + (long)jq * D + 8 * hh);
-        const u32x4* gs = reinterpret_cast<const u32x4*>(dout + base + (long)jq * D + 8 * hh);
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-            u32x4 a = qs[2 * s], g = gs[2 * s];
-            if (q0 + n >= T) g = u32x4{0u, 0u, 0u, 0u};
-            qf[s] = __builtin_bit_cast(bf16x8, a);
-            gf[s] = __builtin_bit_cast(bf16x8, g);
-        }
-    }
-
-    // per-lane LDS offsets inside a tile
-    const int key_l = perm_row(n);
+    // per-lane LDS offsets inside a 32-row subtile
     int aoff[D / 16];                       // A-operand reads (K rows for S^T, V rows for P^T)
+    {
+        const int key_l = perm_row(n);
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s) aoff[s] = tile_off_perm<D>(key_l, 2 * s + hh);
+        for (int s = 0; s < D / 16; ++s) aoff[s] = tile_off_perm<D>(key_l, 2 * s + hh);
+    }
     int ktr[D / 32][2];                     // transposing reads of K for dQ = dZ K
     {
         const int row_l = 16 * (gg >> 1) + (li >> 2);
@@ -167,164 +264,200 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                 ktr[b][t] = tile_off_perm<D>(row_l + 4 * t, 4 * b + cl) + 8 * (li & 1);
     }
 
-    u32x4 kst[C::CPT], vst[C::CPT];
-    auto stage_load = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < C::CPT; ++i) {
-            const int id = tid + i * NTHREADS;
-            const int row = id / C::CPR, c = id % C::CPR;
-            const long gr = min(kt * BK + row, T - 1);
-            kst[i] = *reinterpret_cast<const u32x4*>(Kg + gr * D + c * 8);
-            vst[i] = *reinterpret_cast<const u32x4*>(Vg + gr * D + c * 8);
-        }
-    };
-    auto stage_store = [&](int buf) {
-        char* kb = smem + buf * C::STAGE;
-#pragma unroll
-        for (int i = 0; i < C::CPT; ++i) {
-            const int id = tid + i * NTHREADS;
-            const int row = id / C::CPR, c = id % C::CPR;
-            const int off = tile_off_perm<D>(row, c);
-            *reinterpret_cast<u32x4*>(kb + off) = kst[i];
-            *reinterpret_cast<u32x4*>(kb + C::TILE + off) = vst[i];
-        }
-    };
-
-    f32x16 dqacc[D / 32];
-#pragma unroll
-    for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) dqacc[b][r] = 0.0f;
-
     const float scale = 1.0f / sqrtf((float)D);
     const float c2 = SB_LOG2E * scale;
-    float a2 = -m[bh * (long)T + jq] * SB_LOG2E;   // sum of sp2 from the sweep position up to the query
-    float bsum = 0.0f;                             // sum of G over the keys already passed
     float* const cag = ca + bh * (long)nt32 * T;
     float* const cbg = cb + bh * (long)nt32 * T;
 
-    // ---- sweep over key tiles, left to right
-    const int jmax = min(T, qb * BQ + BQ) - 1;
-    const int ntile = (jmax + BK - 1) / BK;
-    if (ntile > 0) {
-        stage_load(0);
-        stage_store(0);
-    }
-    __syncthreads();
-    for (int kt = 0; kt < ntile; ++kt) {
-        const int buf = kt & 1;
-        const char* kb = smem + buf * C::STAGE;
-        const bool more = kt + 1 < ntile;
-        if (more) stage_load(kt + 1);
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int key0 = kt * BK + 32 * u;
-            if (wave_live && key0 <= q0) {
-                const char* ktile = kb + u * 32 * C::ROW;
-                const char* vtile = ktile + C::TILE;
-                f32x16 sacc, pacc;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; pacc[r] = 0.0f; }
-#pragma unroll
-                for (int s = 0; s < D / 16; ++s) {
-                    const u32x4 kw = *reinterpret_cast<const u32x4*>(ktile + aoff[s]);
-                    const u32x4 vw = *reinterpret_cast<const u32x4*>(vtile + aoff[s]);
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[s], sacc, 0, 0, 0);
-                    pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), gf[s], pacc, 0, 0, 0);
-                }
-                const SubtileOut so = subtile_math<true>(sacc, pacc, a2, bsum, c2, scale, n, hh, key0 == q0);
-                // carries of this (subtile, query) for the key-stationary kernel
-                if (hh == 0 && q0 + n < T) {
-                    const long ci = (long)(key0 >> 5) * T + q0 + n;
-                    cag[ci] = so.ca_right;
-                    cbg[ci] = bsum;
-                }
-                a2 = so.ca_right;
-                bsum += so.g_tot;
-                // dQ += dZ K: dZ from registers, K (rows = keys) through the transposing load
-#pragma unroll
-                for (int b = 0; b < D / 32; ++b) {
-#pragma unroll
-                    for (int s = 0; s < 2; ++s) {
-                        const char* p = ktile + (8 * s) * C::ROW;
-                        const bf16x8 kf = tr_pair(p + ktr[b][0], p + ktr[b][1]);
-                        dqacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(so.pz[s], kf, dqacc[b], 0, 0, 0);
-                    }
-                }
-            }
-            if (u == 0 && more) stage_store(buf ^ 1);
-        }
-        __syncthreads();
-    }
+    bf16x8 qf[D / 16], gf[D / 16];          // B operands: this lane's query row of Q and dO
+    f32x16 dqacc[D / 32];
+    float a2 = 0.0f;                        // sum of sp2 from the sweep position up to the query
+    float bsum = 0.0f;                      // sum of G over the keys already passed
+    int q0 = 0;
+    bool dirty = false;                     // a chain of this lane left its range (fast variant)
 
-    // ---- dQ store: dqacc[b][r] is query row 8*(r/4) + 4*hh + r%4, column 32b + n
-    if (wave_live) {
-        float* dQg = dq + base;
+    // one 32-key subtile at keys key0 .. key0+31
+    auto subtile = [&](auto mask_c, const char* ktile, int key0) __attribute__((always_inline)) {
+        constexpr bool MASK = decltype(mask_c)::value;
+        const char* vtile = ktile + C::TILE;
+        auto s_mfma = [&]() __attribute__((always_inline)) {
+            f32x16 acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+                const u32x4 kw = *reinterpret_cast<const u32x4*>(ktile + aoff[s]);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[s], acc, 0, 0, 0);
+            }
+            return acc;
+        };
+        auto p_mfma = [&]() __attribute__((always_inline)) {
+            f32x16 acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+                const u32x4 vw = *reinterpret_cast<const u32x4*>(vtile + aoff[s]);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), gf[s], acc, 0, 0, 0);
+            }
+            return acc;
+        };
+        SubtileOut so;
+        if constexpr (SLOW) {
+            const f32x16 sacc = s_mfma();
+            const f32x16 pacc = p_mfma();
+            subtile_math_log<true, MASK>(so, sacc, pacc, a2, bsum, c2, n, hh);
+        } else {
+            Chain ch;
+            const f32x16 sacc = s_mfma();
+            dirty |= !subtile_stage1<MASK>(ch, sacc, c2, n, hh);
+            const f32x16 pacc = p_mfma();
+            subtile_stage2<true, false>(so, ch, pacc, a2, bsum, hh);
+        }
+        // carries of this (subtile, query) for the key-stationary kernel
+        if (hh == 0 && q0 + n < T) {
+            const long ci = (long)(key0 >> 5) * T + q0 + n;
+            cag[ci] = so.ca_right;
+            cbg[ci] = bsum;
+        }
+        a2 = so.ca_right;
+        bsum += so.g_tot;
+        // dQ += dZ K: dZ from registers, K (rows = keys) through the transposing load
 #pragma unroll
         for (int b = 0; b < D / 32; ++b) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = q0 + 8 * (r >> 2) + 4 * hh + (r & 3);
-                if (row < T) dQg[(long)row * D + 32 * b + n] = dqacc[b][r];
+            for (int s = 0; s < 2; ++s) {
+                const char* p = ktile + (8 * s) * C::ROW;
+                const bf16x8 kf = tr_pair(p + ktr[b][0], p + ktr[b][1]);
+                dqacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(so.pz[s], kf, dqacc[b], 0, 0, 0);
             }
+        }
+    };
+
+    for (int part = 0; part < 2; ++part) {
+        const int qb = part == 0 ? nqb - 1 - pidx : pidx;
+        if (part == 1 && 2 * pidx == nqb - 1) break;     // odd block count: the middle block is alone
+        if (SLOW && flags[bh * nqb + qb] == 0) continue;  // only the blocks the fast variant flagged
+        const int Q0 = qb * BQ;
+        q0 = Q0 + wave * 32;
+        const bool wave_live = q0 < T;
+        const int jq = min(q0 + n, T - 1);
+        if (tid == 0) s_dirty = 0;
+        dirty = false;
+        barrier_nofence();                               // everyone is done with the stages of the block before
+        {
+            const u32x4* qs = reinterpret_cast<const u32x4*>(q + base + (long)jq * D + 8 * hh);
+            const u32x4* gs = reinterpret_cast<const u32x4*>(dout + base + (long)jq * D + 8 * hh);
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+                u32x4 a = qs[2 * s], g = gs[2 * s];
+                if (q0 + n >= T) g = u32x4{0u, 0u, 0u, 0u};   // rows past T contribute nothing
+                qf[s] = __builtin_bit_cast(bf16x8, a);
+                gf[s] = __builtin_bit_cast(bf16x8, g);
+            }
+        }
+        a2 = -m[bh * (long)T + jq] * SB_LOG2E;
+        bsum = 0.0f;
+        // wait for these loads (and the first block's stores) once, before the staging
+        // loads, which are counted in the same counter behind the compiler's back
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) { asm volatile("" :: "v"(qf[s])); asm volatile("" :: "v"(gf[s])); }
+        asm volatile("" :: "v"(a2));
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dqacc[b][r] = 0.0f;
+
+        // ---- sweep over 64-key tiles, left to right; iteration it handles tile it in buffer it & 1
+        const int kmax = min(T, Q0 + BQ) - 1;            // keys 0 .. kmax-1 are visible to some row
+        const int ntile = (kmax + TK - 1) / TK;
+        const int nclean = min(ntile, Q0 / TK);          // tiles entirely left of the block's rows
+        stage_tile<D, true>(Kg, Vg, 0, T, smem, wave, lane);
+        auto begin_iter = [&](int it) __attribute__((always_inline)) {
+            dma_wait<0>();                               // this wave's share of tile `it` has landed
+            barrier_nofence();                           // ... everyone's has, and tile it-1 is no longer read
+            // past the end tile 0 is loaded once more into the buffer nobody reads
+            stage_tile<D, true>(Kg, Vg, it + 1 < ntile ? it + 1 : 0, T, smem + ((it + 1) & 1) * C::STAGE, wave, lane);
+            return (const char*)(smem + (it & 1) * C::STAGE);
+        };
+        int it = 0;
+        for (; it < nclean; ++it) {                      // fully visible tiles
+            const char* sp = begin_iter(it);
+            subtile(bc<false>{}, sp, it * TK);
+            subtile(bc<false>{}, sp + 32 * C::ROW, it * TK + 32);
+        }
+        for (; it < ntile; ++it) {                       // tiles that touch the diagonal band
+            const char* sp = begin_iter(it);
+            if (wave_live) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int key0 = it * TK + 32 * u;
+                    if (key0 == q0) subtile(bc<true>{}, sp + u * 32 * C::ROW, key0);
+                    else if (key0 < q0) subtile(bc<false>{}, sp + u * 32 * C::ROW, key0);
+                }
+            }
+        }
+        dma_wait<0>();
+
+        // ---- dQ store: dqacc[b][r] is query row 8*(r/4) + 4*hh + r%4, column 32b + n
+        if (wave_live) {
+            float* dQg = dq + base;
+#pragma unroll
+            for (int b = 0; b < D / 32; ++b) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = q0 + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    if (row < T) dQg[(long)row * D + 32 * b + n] = dqacc[b][r] * scale;
+                }
+            }
+        }
+        if constexpr (!SLOW) {
+            if (__builtin_amdgcn_ballot_w64(dirty) != 0 && lane == 0) atomicOr(&s_dirty, 1);
+            __syncthreads();
+            if (tid == 0) flags[bh * nqb + qb] = s_dirty;
         }
     }
 }
 
 // ------------------------------------------------------------------ dK / dV kernel
 template <int D> struct DkvCfg {
-    static constexpr int ROW = D * 2;
-    static constexpr int TILE = 32 * ROW;            // 32 query rows
-    static constexpr int STAGE = 2 * TILE;           // Q tile + dO tile
-    static constexpr int T_OFF = 2 * STAGE;          // after the double buffer
-    static constexpr int T_WAVE = 2 * 32 * TROW;     // A and dZ scratch of one wave
-    static constexpr int LDS_BYTES = T_OFF + 4 * T_WAVE;
-    static constexpr int CPR = D / 8;
-    static constexpr int CPT = (32 * CPR + NTHREADS - 1) / NTHREADS;
+    static constexpr int T_OFF = 2 * StageCfg<D>::STAGE;   // after the double buffer
+    static constexpr int T_WAVE = 2 * 32 * TROW;           // A and dZ scratch of one wave
+    static constexpr int LDS_BYTES = T_OFF + NW * T_WAVE;
 };
 
-template <int D>
+template <int D, bool SLOW>
 __global__ void __launch_bounds__(NTHREADS, 1)
 bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                const uint16_t* __restrict__ v, const uint16_t* __restrict__ dout,
                const float* __restrict__ ca, const float* __restrict__ cb,
-               float* __restrict__ dk, float* __restrict__ dv, int T, int BH, int nkb, int nt32)
+               float* __restrict__ dk, float* __restrict__ dv, int* __restrict__ flags,
+               int T, int BH, int nkb, int nt32)
 {
-    using C = DkvCfg<D>;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    using C = StageCfg<D>;
+    using CK = DkvCfg<D>;
+    __shared__ __attribute__((aligned(1024))) char smem[CK::LDS_BYTES];
+    __shared__ int s_dirty;
 
     const int wg = blockIdx.x;
     const int xcd = wg & 7, slot = wg >> 3;
-    const long bh = xcd + 8L * (slot / nkb);
-    const int kb = slot % nkb;                      // small kb = most later queries = first
+    const int npair = (nkb + 1) >> 1;
+    const long bh = xcd + 8L * (slot / npair);
+    const int pidx = slot % npair;
     if (bh >= BH) return;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, hh = lane >> 5;
     const int gg = lane >> 4, li = lane & 15;
-    const int k0 = kb * BKW + wave * 32;            // this wave's 32 keys
-    const int kt32 = k0 >> 5;
-    const bool wave_live = k0 < T;
 
     const long base = bh * (long)T * D;
     const uint16_t* Qg = q + base;
     const uint16_t* Gg = dout + base;
 
-    // A operands held for the whole kernel: this wave's K and V rows (MFMA row n <- key perm_row(n))
-    bf16x8 kf[D / 16], vf[D / 16];
-    {
-        const long kr = min(k0 + perm_row(n), T - 1);
-        const u32x4* ks = reinterpret_cast<const u32x4*>(k + base + kr * D + 8 * hh);
-        const u32x4* vs = reinterpret_cast<const u32x4*>(v + base + kr * D + 8 * hh);
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-            kf[s] = __builtin_bit_cast(bf16x8, ks[2 * s]);
-            vf[s] = __builtin_bit_cast(bf16x8, vs[2 * s]);
-        }
-    }
-
-    // per-lane LDS offsets inside a 32-row Q / dO tile (natural row order)
+    // per-lane LDS offsets inside a 32-row Q / dO subtile (natural row order)
     int boff[D / 16];                       // B-operand reads: row = query n
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) boff[s] = tile_off_nat<D>(n, 2 * s + hh);
@@ -338,159 +471,212 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             for (int t = 0; t < 2; ++t)
                 qtr[b][t] = tile_off_nat<D>(row_l + 4 * t, 4 * b + cl) + 8 * (li & 1);
     }
-    char* const scr = smem + C::T_OFF + wave * C::T_WAVE;                 // [2][32][TROW]
+    char* const scr = smem + CK::T_OFF + wave * CK::T_WAVE;               // [2][32][TROW]
     const int sw_off = n * TROW + 32 * hh;                                // scratch write: row = query n
     const int st_off = (8 * (gg >> 1) + (li >> 2)) * TROW + (16 * (gg & 1) + 4 * (li & 3)) * 2;
 
-    u32x4 qst[C::CPT], gst[C::CPT];
-    auto stage_load = [&](int qs) {
-#pragma unroll
-        for (int i = 0; i < C::CPT; ++i) {
-            const int id = tid + i * NTHREADS;
-            if (id < 32 * C::CPR) {
-                const int row = id / C::CPR, c = id % C::CPR;
-                const int j = qs * 32 + row;
-                const long gr = min(j, T - 1);
-                qst[i] = *reinterpret_cast<const u32x4*>(Qg + gr * D + c * 8);
-                gst[i] = *reinterpret_cast<const u32x4*>(Gg + gr * D + c * 8);
-                if (j >= T) gst[i] = u32x4{0u, 0u, 0u, 0u};
-            }
-        }
-    };
-    auto stage_store = [&](int buf) {
-        char* qb = smem + buf * C::STAGE;
-#pragma unroll
-        for (int i = 0; i < C::CPT; ++i) {
-            const int id = tid + i * NTHREADS;
-            if (id < 32 * C::CPR) {
-                const int row = id / C::CPR, c = id % C::CPR;
-                const int off = tile_off_nat<D>(row, c);
-                *reinterpret_cast<u32x4*>(qb + off) = qst[i];
-                *reinterpret_cast<u32x4*>(qb + C::TILE + off) = gst[i];
-            }
-        }
-    };
-
-    f32x16 dkacc[D / 32], dvacc[D / 32];
-#pragma unroll
-    for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { dkacc[b][r] = 0.0f; dvacc[b][r] = 0.0f; }
-
     const float scale = 1.0f / sqrtf((float)D);
     const float c2 = SB_LOG2E * scale;
-    const float* const cag = ca + (bh * (long)nt32 + kt32) * T;
-    const float* const cbg = cb + (bh * (long)nt32 + kt32) * T;
 
-    // ---- sweep over 32-row query blocks, from the workgroup's diagonal to the end
-    const int qs_begin = kb * (BKW / 32);
-    if (qs_begin < nt32) {
-        stage_load(qs_begin);
-        stage_store(0);
-    }
-    __syncthreads();
-    for (int qs = qs_begin; qs < nt32; ++qs) {
-        const int buf = (qs - qs_begin) & 1;
-        const char* qtile = smem + buf * C::STAGE;
+    bf16x8 kf[D / 16], vf[D / 16];          // A operands: this wave's K and V rows (MFMA row n <- key perm_row(n))
+    f32x16 dkacc[D / 32], dvacc[D / 32];
+    const float* cag = nullptr;
+    const float* cbg = nullptr;
+    bool dirty = false;                     // a chain of this lane left its range (fast variant)
+
+    // one 32-query subtile at query rows j0 .. j0+31
+    auto subtile = [&](auto mask_c, const char* qtile, int j0) __attribute__((always_inline)) {
+        constexpr bool MASK = decltype(mask_c)::value;
         const char* gtile = qtile + C::TILE;
-        const bool more = qs + 1 < nt32;
-        if (more) stage_load(qs + 1);
-        if (wave_live && qs >= kt32) {
-            f32x16 sacc, pacc;
+        auto s_mfma = [&]() __attribute__((always_inline)) {
+            f32x16 acc;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; pacc[r] = 0.0f; }
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 #pragma unroll
             for (int s = 0; s < D / 16; ++s) {
                 const u32x4 qw = *reinterpret_cast<const u32x4*>(qtile + boff[s]);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], __builtin_bit_cast(bf16x8, qw), acc, 0, 0, 0);
+            }
+            return acc;
+        };
+        auto p_mfma = [&]() __attribute__((always_inline)) {
+            f32x16 acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
                 const u32x4 gw = *reinterpret_cast<const u32x4*>(gtile + boff[s]);
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], __builtin_bit_cast(bf16x8, qw), sacc, 0, 0, 0);
-                pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s], __builtin_bit_cast(bf16x8, gw), pacc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s], __builtin_bit_cast(bf16x8, gw), acc, 0, 0, 0);
             }
-            const int j = qs * 32 + n;
-            const int jc = min(j, T - 1);
-            const float car = cag[jc];
-            const float cbl = (j < T) ? cbg[jc] : 0.0f;    // rows past T must give dZ = 0
-            const SubtileOut so = subtile_math<false>(sacc, pacc, car, cbl, c2, scale, n, hh, qs == kt32);
-
-            // A and dZ into [key][query] operand layout through the wave's scratch
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            *reinterpret_cast<bf16x8*>(scr + sw_off) = so.pa[0];
-            *reinterpret_cast<bf16x8*>(scr + sw_off + 16) = so.pa[1];
-            *reinterpret_cast<bf16x8*>(scr + 32 * TROW + sw_off) = so.pz[0];
-            *reinterpret_cast<bf16x8*>(scr + 32 * TROW + sw_off + 16) = so.pz[1];
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            bf16x8 at[2], zt[2];
-#pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                const char* pa = scr + (16 * s2) * TROW + st_off;
-                const char* pz = pa + 32 * TROW;
-                at[s2] = tr_pair(pa, pa + 4 * TROW);
-                zt[s2] = tr_pair(pz, pz + 4 * TROW);
-            }
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-
-            // dV += A^T dO, dK += dZ^T Q: K-dim = the 32 queries, B operands through the transposing load
-#pragma unroll
-            for (int b = 0; b < D / 32; ++b) {
-#pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2) {
-                    const int ro = (16 * s2) * C::ROW;
-                    const bf16x8 gop = tr_pair(gtile + ro + qtr[b][0], gtile + ro + qtr[b][1]);
-                    const bf16x8 qop = tr_pair(qtile + ro + qtr[b][0], qtile + ro + qtr[b][1]);
-                    dvacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at[s2], gop, dvacc[b], 0, 0, 0);
-                    dkacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zt[s2], qop, dkacc[b], 0, 0, 0);
-                }
-            }
+            return acc;
+        };
+        const int j = j0 + n;
+        const int jc = min(j, T - 1);
+        // rows past T: an infinite carry gives A = 0 and G = 0, and with cb = 0 also dZ = 0
+        const float car = (j < T) ? cag[jc] : INFINITY;
+        const float cbl = (j < T) ? cbg[jc] : 0.0f;
+        SubtileOut so;
+        if constexpr (SLOW) {
+            const f32x16 sacc = s_mfma();
+            const f32x16 pacc = p_mfma();
+            subtile_math_log<false, MASK>(so, sacc, pacc, car, cbl, c2, n, hh);
+        } else {
+            Chain ch;
+            const f32x16 sacc = s_mfma();
+            dirty |= !subtile_stage1<MASK>(ch, sacc, c2, n, hh);
+            const f32x16 pacc = p_mfma();
+            subtile_stage2<false, true>(so, ch, pacc, car, cbl, hh);
         }
-        if (more) stage_store(buf ^ 1);
-        __syncthreads();
-    }
 
-    // ---- store: acc[b][r] is key row k0 + 8*(r/4) + 4*hh + r%4, column 32b + n
-    if (wave_live) {
-        float* dKg = dk + base;
-        float* dVg = dv + base;
+        // A and dZ into [key][query] operand layout through the wave's scratch
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        *reinterpret_cast<bf16x8*>(scr + sw_off) = so.pa[0];
+        *reinterpret_cast<bf16x8*>(scr + sw_off + 16) = so.pa[1];
+        *reinterpret_cast<bf16x8*>(scr + 32 * TROW + sw_off) = so.pz[0];
+        *reinterpret_cast<bf16x8*>(scr + 32 * TROW + sw_off + 16) = so.pz[1];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        bf16x8 at[2], zt[2];
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const char* pa = scr + (16 * s2) * TROW + st_off;
+            const char* pz = pa + 32 * TROW;
+            at[s2] = tr_pair(pa, pa + 4 * TROW);
+            zt[s2] = tr_pair(pz, pz + 4 * TROW);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+
+        // dV += A^T dO, dK += dZ^T Q: K-dim = the 32 queries, B operands through the transposing load
 #pragma unroll
         for (int b = 0; b < D / 32; ++b) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = k0 + 8 * (r >> 2) + 4 * hh + (r & 3);
-                if (key < T) {
-                    dKg[(long)key * D + 32 * b + n] = dkacc[b][r];
-                    dVg[(long)key * D + 32 * b + n] = dvacc[b][r];
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const int ro = (16 * s2) * C::ROW;
+                const bf16x8 gop = tr_pair(gtile + ro + qtr[b][0], gtile + ro + qtr[b][1]);
+                const bf16x8 qop = tr_pair(qtile + ro + qtr[b][0], qtile + ro + qtr[b][1]);
+                dvacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at[s2], gop, dvacc[b], 0, 0, 0);
+                dkacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zt[s2], qop, dkacc[b], 0, 0, 0);
+            }
+        }
+    };
+
+    for (int part = 0; part < 2; ++part) {
+        const int kb = part == 0 ? pidx : nkb - 1 - pidx;    // small kb = most later queries = first
+        if (part == 1 && 2 * pidx == nkb - 1) break;
+        if (SLOW && flags[bh * nkb + kb] == 0) continue;     // only the blocks the fast variant flagged
+        const int K0 = kb * BKW;
+        const int k0 = K0 + wave * 32;                       // this wave's 32 keys
+        const int kt32 = k0 >> 5;
+        const bool wave_live = k0 < T;
+        if (tid == 0) s_dirty = 0;
+        dirty = false;
+        barrier_nofence();                                   // everyone is done with the stages of the block before
+        {
+            const long kr = min(k0 + perm_row(n), T - 1);
+            const u32x4* ks = reinterpret_cast<const u32x4*>(k + base + kr * D + 8 * hh);
+            const u32x4* vs = reinterpret_cast<const u32x4*>(v + base + kr * D + 8 * hh);
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+                kf[s] = __builtin_bit_cast(bf16x8, ks[2 * s]);
+                vf[s] = __builtin_bit_cast(bf16x8, vs[2 * s]);
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) { asm volatile("" :: "v"(kf[s])); asm volatile("" :: "v"(vf[s])); }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { dkacc[b][r] = 0.0f; dvacc[b][r] = 0.0f; }
+        cag = ca + (bh * (long)nt32 + kt32) * T;
+        cbg = cb + (bh * (long)nt32 + kt32) * T;
+
+        // ---- sweep over 64-row query tiles, from the block's diagonal to the end;
+        // iteration it handles tile jt0 + it in buffer it & 1
+        const int jt0 = K0 / TK;
+        const int ntile = max((T + TK - 1) / TK - jt0, 0);
+        const int ndiag = min(ntile, BKW / TK);              // tiles that touch the diagonal band
+        if (ntile > 0) stage_tile<D, false>(Qg, Gg, jt0, T, smem, wave, lane);
+        auto begin_iter = [&](int it) __attribute__((always_inline)) {
+            dma_wait<0>();
+            barrier_nofence();
+            stage_tile<D, false>(Qg, Gg, it + 1 < ntile ? jt0 + it + 1 : jt0, T, smem + ((it + 1) & 1) * C::STAGE, wave, lane);
+            return (const char*)(smem + (it & 1) * C::STAGE);
+        };
+        int it = 0;
+        for (; it < ndiag; ++it) {
+            const char* sp = begin_iter(it);
+            if (wave_live) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int j0 = (jt0 + it) * TK + 32 * u;
+                    if (j0 == k0) subtile(bc<true>{}, sp + u * 32 * C::ROW, j0);
+                    else if (j0 > k0 && j0 < T) subtile(bc<false>{}, sp + u * 32 * C::ROW, j0);
                 }
             }
+        }
+        for (; it < ntile; ++it) {
+            const char* sp = begin_iter(it);
+            if (wave_live) {
+                const int j0 = (jt0 + it) * TK;
+                subtile(bc<false>{}, sp, j0);
+                if (j0 + 32 < T) subtile(bc<false>{}, sp + 32 * C::ROW, j0 + 32);
+            }
+        }
+        dma_wait<0>();
+
+        // ---- store: acc[b][r] is key row k0 + 8*(r/4) + 4*hh + r%4, column 32b + n
+        if (wave_live) {
+            float* dKg = dk + base;
+            float* dVg = dv + base;
+#pragma unroll
+            for (int b = 0; b < D / 32; ++b) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = k0 + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    if (key < T) {
+                        dKg[(long)key * D + 32 * b + n] = dkacc[b][r] * scale;
+                        dVg[(long)key * D + 32 * b + n] = dvacc[b][r];
+                    }
+                }
+            }
+        }
+        if constexpr (!SLOW) {
+            if (__builtin_amdgcn_ballot_w64(dirty) != 0 && lane == 0) atomicOr(&s_dirty, 1);
+            __syncthreads();
+            if (tid == 0) flags[bh * nkb + kb] = s_dirty;
         }
     }
 }
 
+// workspace layout: ca[BH][nt32][T], cb[BH][nt32][T] (fp32), then the per-block flags of
+// the two kernels (int): [BH][nqb], [BH][nkb]
 template <int D>
 hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, const float* m,
                       const uint16_t* dout, float* dq, float* dk, float* dv, float* workspace,
                       int BH, int T, hipStream_t stream)
 {
-    auto kq = bwd_dq_kernel<D>;
-    auto kkv = bwd_dkv_kernel<D>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kq),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, DqCfg<D>::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kkv),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, DkvCfg<D>::LDS_BYTES);
-    if (e != hipSuccess) return e;
     const int nt32 = (T + 31) / 32;
-    float* ca = workspace;
-    float* cb = workspace + (long)BH * nt32 * T;
     const int nqb = (T + BQ - 1) / BQ;
     const int nkb = (T + BKW - 1) / BKW;
-    const long bq = 8L * ((BH + 7) / 8) * nqb;
-    const long bk = 8L * ((BH + 7) / 8) * nkb;
+    float* ca = workspace;
+    float* cb = ca + (long)BH * nt32 * T;
+    int* fq = reinterpret_cast<int*>(cb + (long)BH * nt32 * T);
+    int* fk = fq + (long)BH * nqb;
+    const long bq = 8L * ((BH + 7) / 8) * ((nqb + 1) / 2);
+    const long bk = 8L * ((BH + 7) / 8) * ((nkb + 1) / 2);
     if (bq > 0x7fffffffL || bk > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kq, dim3((unsigned)bq), dim3(NTHREADS), DqCfg<D>::LDS_BYTES, stream,
-                       q, k, v, m, dout, dq, ca, cb, T, BH, nqb, nt32);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kkv, dim3((unsigned)bk), dim3(NTHREADS), DkvCfg<D>::LDS_BYTES, stream,
-                       q, k, v, dout, ca, cb, dk, dv, T, BH, nkb, nt32);
+    hipError_t e;
+    hipLaunchKernelGGL((bwd_dq_kernel<D, false>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
+                       q, k, v, m, dout, dq, ca, cb, fq, T, BH, nqb, nt32);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL((bwd_dq_kernel<D, true>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
+                       q, k, v, m, dout, dq, ca, cb, fq, T, BH, nqb, nt32);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL((bwd_dkv_kernel<D, false>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
+                       q, k, v, dout, ca, cb, dk, dv, fk, T, BH, nkb, nt32);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL((bwd_dkv_kernel<D, true>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
+                       q, k, v, dout, ca, cb, dk, dv, fk, T, BH, nkb, nt32);
     return hipGetLastError();
 }
 
@@ -499,7 +685,8 @@ hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, c
 size_t bwd_workspace_bytes(int B, int H, int T)
 {
     const size_t nt32 = (size_t)(T + 31) / 32;
-    return 2 * sizeof(float) * (size_t)B * H * nt32 * T;
+    const size_t nblk = (size_t)(T + BQ - 1) / BQ + (size_t)(T + BKW - 1) / BKW;
+    return (2 * sizeof(float) * nt32 * T + sizeof(int) * nblk) * (size_t)B * H;
 }
 
 hipError_t launch_bwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const float* m,
