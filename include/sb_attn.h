@@ -75,8 +75,9 @@ int sb_attn_fwd_f32(const float* q, const float* k, const float* v, float* o, fl
  * workspace: caller-owned device scratch of at least
  * sb_attn_bwd_workspace_bytes(B,H,T,d) bytes, 16-byte aligned; its contents on
  * entry do not matter and are garbage afterwards.  It holds two floats per
- * (query row, 32-key strip): 8*B*H*T*ceil(T/32) bytes.  SB_ERR_WORKSPACE if it
- * is NULL or too small.  sb_attn_bwd_workspace_bytes returns 0 for a bad shape.
+ * (query row, 32-key strip) and one int per 128-row block of queries and of keys:
+ * B*H*(8*T*ceil(T/32) + 8*ceil(T/128)) bytes.  SB_ERR_WORKSPACE if it is NULL or
+ * too small.  sb_attn_bwd_workspace_bytes returns 0 for a bad shape.
  * No atomics are used: results are bit-reproducible from run to run.
  */
 size_t sb_attn_bwd_workspace_bytes(int B, int H, int T, int d);

@@ -62,7 +62,8 @@ def test_argument_validation_without_a_gpu(lib):
     assert lib.sb_attn_bwd(p, p, p, p, p, p, p, p, None, 0, 1, 1, 8, 32, None) == -3
     # workspace: size query, then missing / too small / misaligned workspace
     need = lib.sb_attn_bwd_workspace_bytes(2, 3, 100, 64)
-    assert need == 8 * 2 * 3 * 100 * 4          # two floats per (row, 32-key strip)
+    # two floats per (row, 32-key strip) and one int per 128-row query block and key block
+    assert need == 2 * 3 * (8 * 100 * 4 + 4 * (1 + 1))
     assert lib.sb_attn_bwd_workspace_bytes(2, 3, 100, 65) == 0
     assert lib.sb_attn_bwd(p, p, p, p, p, p, p, p, None, 0, 2, 3, 100, 64, None) == -6
     assert lib.sb_attn_bwd(p, p, p, p, p, p, p, p, p, need - 1, 2, 3, 100, 64, None) == -6
