@@ -191,26 +191,42 @@ template <int D> struct StageCfg {
     static constexpr int NPW = TILE / 1024 / NW;        // loads per wave per tile
 };
 
+// goff[i]: byte offset inside a tile of the 16 B this lane fetches with its i-th load
 template <int D, bool PERM>
-__device__ __forceinline__ void stage_tile(const uint16_t* X, const uint16_t* Y, int jt, int T, char* sp,
-                                           int wave, int lane)
+__device__ __forceinline__ void stage_offsets(int (&goff)[StageCfg<D>::NPW], int wave, int lane)
 {
     using C = StageCfg<D>;
-    const bool full = (jt + 1) * TK <= T;
 #pragma unroll
-    for (int m = 0; m < 2; ++m) {
-        const uint16_t* G = m == 0 ? X : Y;
-        char* base = sp + m * C::TILE;
+    for (int i = 0; i < C::NPW; ++i) {
+        const int row = (wave * C::NPW + i) * C::BLK_ROWS + lane / C::CPR;
+        const int swz = PERM ? swz_perm<D>(row) : swz_nat<D>(row);
+        goff[i] = (row * D + (((lane % C::CPR) ^ swz) << 3)) * 2;
+    }
+}
+
+template <int D, bool PERM>
+__device__ __forceinline__ void stage_tile(const uint16_t* X, const uint16_t* Y, int jt, int T, char* sp,
+                                           const int (&goff)[StageCfg<D>::NPW], int wave, int lane)
+{
+    using C = StageCfg<D>;
+    if ((jt + 1) * TK <= T) {                           // all 64 rows exist
+        const uint16_t* xb = X + (long)jt * TK * D;
+        const uint16_t* yb = Y + (long)jt * TK * D;
 #pragma unroll
-        for (int i = 0; i < C::NPW; ++i) {
-            const int row = (wave * C::NPW + i) * C::BLK_ROWS + lane / C::CPR;
-            const int swz = PERM ? swz_perm<D>(row) : swz_nat<D>(row);
-            const int c = (lane % C::CPR) ^ swz;
-            if (full) {
-                dma16_to_lds_saddr(G + (long)jt * TK * D, (row * D + c * 8) * 2, base + (wave * C::NPW + i) * 1024);
-            } else {                                    // rows past T are clamped (their results are masked)
+        for (int i = 0; i < C::NPW; ++i) dma16_to_lds_saddr(xb, goff[i], sp + (wave * C::NPW + i) * 1024);
+#pragma unroll
+        for (int i = 0; i < C::NPW; ++i) dma16_to_lds_saddr(yb, goff[i], sp + C::TILE + (wave * C::NPW + i) * 1024);
+    } else {                                            // rows past T are clamped (their results are masked)
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const uint16_t* G = m == 0 ? X : Y;
+#pragma unroll
+            for (int i = 0; i < C::NPW; ++i) {
+                const int row = (wave * C::NPW + i) * C::BLK_ROWS + lane / C::CPR;
+                const int swz = PERM ? swz_perm<D>(row) : swz_nat<D>(row);
+                const int c = (lane % C::CPR) ^ swz;
                 const long gr = min(jt * TK + row, T - 1);
-                dma16_to_lds(G + gr * D + c * 8, base + (wave * C::NPW + i) * 1024);
+                dma16_to_lds(G + gr * D + c * 8, sp + m * C::TILE + (wave * C::NPW + i) * 1024);
             }
         }
     }
@@ -263,6 +279,8 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             for (int t = 0; t < 2; ++t)
                 ktr[b][t] = tile_off_perm<D>(row_l + 4 * t, 4 * b + cl) + 8 * (li & 1);
     }
+    int goff[C::NPW];
+    stage_offsets<D, true>(goff, wave, lane);
 
     const float scale = 1.0f / sqrtf((float)D);
     const float c2 = SB_LOG2E * scale;
@@ -373,12 +391,12 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         const int kmax = min(T, Q0 + BQ) - 1;            // keys 0 .. kmax-1 are visible to some row
         const int ntile = (kmax + TK - 1) / TK;
         const int nclean = min(ntile, Q0 / TK);          // tiles entirely left of the block's rows
-        stage_tile<D, true>(Kg, Vg, 0, T, smem, wave, lane);
+        stage_tile<D, true>(Kg, Vg, 0, T, smem, goff, wave, lane);
         auto begin_iter = [&](int it) __attribute__((always_inline)) {
             dma_wait<0>();                               // this wave's share of tile `it` has landed
             barrier_nofence();                           // ... everyone's has, and tile it-1 is no longer read
             // past the end tile 0 is loaded once more into the buffer nobody reads
-            stage_tile<D, true>(Kg, Vg, it + 1 < ntile ? it + 1 : 0, T, smem + ((it + 1) & 1) * C::STAGE, wave, lane);
+            stage_tile<D, true>(Kg, Vg, it + 1 < ntile ? it + 1 : 0, T, smem + ((it + 1) & 1) * C::STAGE, goff, wave, lane);
             return (const char*)(smem + (it & 1) * C::STAGE);
         };
         int it = 0;
@@ -471,6 +489,8 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             for (int t = 0; t < 2; ++t)
                 qtr[b][t] = tile_off_nat<D>(row_l + 4 * t, 4 * b + cl) + 8 * (li & 1);
     }
+    int goff[C::NPW];
+    stage_offsets<D, false>(goff, wave, lane);
     char* const scr = smem + CK::T_OFF + wave * CK::T_WAVE;               // [2][32][TROW]
     const int sw_off = n * TROW + 32 * hh;                                // scratch write: row = query n
     const int st_off = (8 * (gg >> 1) + (li >> 2)) * TROW + (16 * (gg & 1) + 4 * (li & 3)) * 2;
@@ -485,57 +505,34 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     bool dirty = false;                     // a chain of this lane left its range (fast variant)
 
     // one 32-query subtile at query rows j0 .. j0+31
-    auto subtile = [&](auto mask_c, const char* qtile, int j0) __attribute__((always_inline)) {
-        constexpr bool MASK = decltype(mask_c)::value;
+    // the steps of one 32-query subtile (Q rows at qtile, dO rows C::TILE further).  All
+    // operand reads of a step are issued before its first MFMA, so that the LDS latency
+    // is paid once per step and not once per MFMA.
+    // S^T = K Q^T and P^T = V dO^T (two independent accumulation chains, interleaved)
+    auto sp_mfma = [&](const char* qtile, f32x16& sacc, f32x16& pacc) __attribute__((always_inline)) {
         const char* gtile = qtile + C::TILE;
-        auto s_mfma = [&]() __attribute__((always_inline)) {
-            f32x16 acc;
+        u32x4 qw[D / 16], gw[D / 16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-#pragma unroll
-            for (int s = 0; s < D / 16; ++s) {
-                const u32x4 qw = *reinterpret_cast<const u32x4*>(qtile + boff[s]);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], __builtin_bit_cast(bf16x8, qw), acc, 0, 0, 0);
-            }
-            return acc;
-        };
-        auto p_mfma = [&]() __attribute__((always_inline)) {
-            f32x16 acc;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-#pragma unroll
-            for (int s = 0; s < D / 16; ++s) {
-                const u32x4 gw = *reinterpret_cast<const u32x4*>(gtile + boff[s]);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s], __builtin_bit_cast(bf16x8, gw), acc, 0, 0, 0);
-            }
-            return acc;
-        };
-        const int j = j0 + n;
-        const int jc = min(j, T - 1);
-        // rows past T: an infinite carry gives A = 0 and G = 0, and with cb = 0 also dZ = 0
-        const float car = (j < T) ? cag[jc] : INFINITY;
-        const float cbl = (j < T) ? cbg[jc] : 0.0f;
-        SubtileOut so;
-        if constexpr (SLOW) {
-            const f32x16 sacc = s_mfma();
-            const f32x16 pacc = p_mfma();
-            subtile_math_log<false, MASK>(so, sacc, pacc, car, cbl, c2, n, hh);
-        } else {
-            Chain ch;
-            const f32x16 sacc = s_mfma();
-            dirty |= !subtile_stage1<MASK>(ch, sacc, c2, n, hh);
-            const f32x16 pacc = p_mfma();
-            subtile_stage2<false, true>(so, ch, pacc, car, cbl, hh);
+        for (int s = 0; s < D / 16; ++s) {
+            qw[s] = *reinterpret_cast<const u32x4*>(qtile + boff[s]);
+            gw[s] = *reinterpret_cast<const u32x4*>(gtile + boff[s]);
         }
-
-        // A and dZ into [key][query] operand layout through the wave's scratch
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; pacc[r] = 0.0f; }
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], __builtin_bit_cast(bf16x8, qw[s]), sacc, 0, 0, 0);
+            pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s], __builtin_bit_cast(bf16x8, gw[s]), pacc, 0, 0, 0);
+        }
+    };
+    // A and dZ into [key][query] operand layout through the wave's scratch
+    auto transpose = [&](const SubtileOut& so, bf16x8 (&at)[2], bf16x8 (&zt)[2]) __attribute__((always_inline)) {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         *reinterpret_cast<bf16x8*>(scr + sw_off) = so.pa[0];
         *reinterpret_cast<bf16x8*>(scr + sw_off + 16) = so.pa[1];
         *reinterpret_cast<bf16x8*>(scr + 32 * TROW + sw_off) = so.pz[0];
         *reinterpret_cast<bf16x8*>(scr + 32 * TROW + sw_off + 16) = so.pz[1];
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        bf16x8 at[2], zt[2];
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
             const char* pa = scr + (16 * s2) * TROW + st_off;
@@ -544,19 +541,46 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             zt[s2] = tr_pair(pz, pz + 4 * TROW);
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-
-        // dV += A^T dO, dK += dZ^T Q: K-dim = the 32 queries, B operands through the transposing load
+    };
+    // dV += A^T dO, dK += dZ^T Q: K-dim = the 32 queries, B operands through the transposing load
+    auto mm2_fetch = [&](const char* qtile, bf16x8 (&gop)[D / 16], bf16x8 (&qop)[D / 16]) __attribute__((always_inline)) {
+        const char* gtile = qtile + C::TILE;
 #pragma unroll
-        for (int b = 0; b < D / 32; ++b) {
+        for (int b = 0; b < D / 32; ++b)
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
                 const int ro = (16 * s2) * C::ROW;
-                const bf16x8 gop = tr_pair(gtile + ro + qtr[b][0], gtile + ro + qtr[b][1]);
-                const bf16x8 qop = tr_pair(qtile + ro + qtr[b][0], qtile + ro + qtr[b][1]);
-                dvacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at[s2], gop, dvacc[b], 0, 0, 0);
-                dkacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zt[s2], qop, dkacc[b], 0, 0, 0);
+                gop[2 * b + s2] = tr_pair(gtile + ro + qtr[b][0], gtile + ro + qtr[b][1]);
+                qop[2 * b + s2] = tr_pair(qtile + ro + qtr[b][0], qtile + ro + qtr[b][1]);
             }
+    };
+    auto mm2 = [&](const bf16x8 (&gop)[D / 16], const bf16x8 (&qop)[D / 16], const bf16x8 (&at)[2], const bf16x8 (&zt)[2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                dvacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at[s2], gop[2 * b + s2], dvacc[b], 0, 0, 0);
+                dkacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zt[s2], qop[2 * b + s2], dkacc[b], 0, 0, 0);
+            }
+    };
+    // one 32-query subtile, start to end
+    auto subtile = [&](auto mask_c, const char* qtile, float car, float cbl) __attribute__((always_inline)) {
+        constexpr bool MASK = decltype(mask_c)::value;
+        SubtileOut so;
+        f32x16 sacc, pacc;
+        sp_mfma(qtile, sacc, pacc);
+        bf16x8 gop[D / 16], qop[D / 16];
+        mm2_fetch(qtile, gop, qop);                          // lands during the element-wise work
+        if constexpr (SLOW) {
+            subtile_math_log<false, MASK>(so, sacc, pacc, car, cbl, c2, n, hh);
+        } else {
+            Chain ch;
+            dirty |= !subtile_stage1<MASK>(ch, sacc, c2, n, hh);
+            subtile_stage2<false, true>(so, ch, pacc, car, cbl, hh);
         }
+        bf16x8 at[2], zt[2];
+        transpose(so, at, zt);
+        mm2(gop, qop, at, zt);
     };
 
     for (int part = 0; part < 2; ++part) {
@@ -591,15 +615,35 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         cbg = cb + (bh * (long)nt32 + kt32) * T;
 
         // ---- sweep over 64-row query tiles, from the block's diagonal to the end;
-        // iteration it handles tile jt0 + it in buffer it & 1
+        // iteration it handles tile jt0 + it in buffer it & 1.  The carries of a tile are
+        // fetched one iteration ahead, and BEFORE the staging loads of that iteration are
+        // issued: vector memory operations complete in order, so a wait for a carry
+        // issued after the staging loads would wait for those as well.
         const int jt0 = K0 / TK;
         const int ntile = max((T + TK - 1) / TK - jt0, 0);
         const int ndiag = min(ntile, BKW / TK);              // tiles that touch the diagonal band
-        if (ntile > 0) stage_tile<D, false>(Qg, Gg, jt0, T, smem, wave, lane);
+        float cn[2][2];                                      // [subtile][ca, cb] of the next tile
+        auto load_carries = [&](int jt) __attribute__((always_inline)) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int j = jt * TK + 32 * u + n;
+                // rows past T: an infinite carry gives A = 0 and G = 0, and with cb = 0 also dZ = 0
+                cn[u][0] = (j < T) ? cag[j] : INFINITY;
+                cn[u][1] = (j < T) ? cbg[j] : 0.0f;
+            }
+        };
+        if (ntile > 0) {
+            load_carries(jt0);
+            stage_tile<D, false>(Qg, Gg, jt0, T, smem, goff, wave, lane);
+        }
+        float cc[2][2];
         auto begin_iter = [&](int it) __attribute__((always_inline)) {
             dma_wait<0>();
             barrier_nofence();
-            stage_tile<D, false>(Qg, Gg, it + 1 < ntile ? jt0 + it + 1 : jt0, T, smem + ((it + 1) & 1) * C::STAGE, wave, lane);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) { cc[u][0] = cn[u][0]; cc[u][1] = cn[u][1]; }
+            if (it + 1 < ntile) load_carries(jt0 + it + 1);
+            stage_tile<D, false>(Qg, Gg, it + 1 < ntile ? jt0 + it + 1 : jt0, T, smem + ((it + 1) & 1) * C::STAGE, goff, wave, lane);
             return (const char*)(smem + (it & 1) * C::STAGE);
         };
         int it = 0;
@@ -609,8 +653,8 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     const int j0 = (jt0 + it) * TK + 32 * u;
-                    if (j0 == k0) subtile(bc<true>{}, sp + u * 32 * C::ROW, j0);
-                    else if (j0 > k0 && j0 < T) subtile(bc<false>{}, sp + u * 32 * C::ROW, j0);
+                    if (j0 == k0) subtile(bc<true>{}, sp + u * 32 * C::ROW, cc[u][0], cc[u][1]);
+                    else if (j0 > k0 && j0 < T) subtile(bc<false>{}, sp + u * 32 * C::ROW, cc[u][0], cc[u][1]);
                 }
             }
         }
@@ -618,8 +662,8 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             const char* sp = begin_iter(it);
             if (wave_live) {
                 const int j0 = (jt0 + it) * TK;
-                subtile(bc<false>{}, sp, j0);
-                if (j0 + 32 < T) subtile(bc<false>{}, sp + 32 * C::ROW, j0 + 32);
+                subtile(bc<false>{}, sp, cc[0][0], cc[0][1]);
+                if (j0 + 32 < T) subtile(bc<false>{}, sp + 32 * C::ROW, cc[1][0], cc[1][1]);
             }
         }
         dma_wait<0>();
