@@ -298,26 +298,30 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     auto subtile = [&](auto mask_c, const char* ktile, int key0) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_c)::value;
         const char* vtile = ktile + C::TILE;
+        // the operand reads of a product are issued before its first MFMA: the LDS latency
+        // is then paid once per product, not once per MFMA
         auto s_mfma = [&]() __attribute__((always_inline)) {
+            u32x4 kw[D / 16];
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) kw[s] = *reinterpret_cast<const u32x4*>(ktile + aoff[s]);
             f32x16 acc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 #pragma unroll
-            for (int s = 0; s < D / 16; ++s) {
-                const u32x4 kw = *reinterpret_cast<const u32x4*>(ktile + aoff[s]);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[s], acc, 0, 0, 0);
-            }
+            for (int s = 0; s < D / 16; ++s)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw[s]), qf[s], acc, 0, 0, 0);
             return acc;
         };
         auto p_mfma = [&]() __attribute__((always_inline)) {
+            u32x4 vw[D / 16];
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) vw[s] = *reinterpret_cast<const u32x4*>(vtile + aoff[s]);
             f32x16 acc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 #pragma unroll
-            for (int s = 0; s < D / 16; ++s) {
-                const u32x4 vw = *reinterpret_cast<const u32x4*>(vtile + aoff[s]);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), gf[s], acc, 0, 0, 0);
-            }
+            for (int s = 0; s < D / 16; ++s)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw[s]), gf[s], acc, 0, 0, 0);
             return acc;
         };
         SubtileOut so;
@@ -341,15 +345,19 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         a2 = so.ca_right;
         bsum += so.g_tot;
         // dQ += dZ K: dZ from registers, K (rows = keys) through the transposing load
+        bf16x8 kt[D / 16];
 #pragma unroll
-        for (int b = 0; b < D / 32; ++b) {
+        for (int b = 0; b < D / 32; ++b)
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 const char* p = ktile + (8 * s) * C::ROW;
-                const bf16x8 kf = tr_pair(p + ktr[b][0], p + ktr[b][1]);
-                dqacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(so.pz[s], kf, dqacc[b], 0, 0, 0);
+                kt[2 * b + s] = tr_pair(p + ktr[b][0], p + ktr[b][1]);
             }
-        }
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                dqacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(so.pz[s], kt[2 * b + s], dqacc[b], 0, 0, 0);
     };
 
     for (int part = 0; part < 2; ++part) {
