@@ -7,13 +7,20 @@ A step is one pass of the hot path over one synthetic batch of the headline
 workload (bf16, B=8, H=16, T=4096, d_head=128; half the heads with k*3): the
 training forward (o and m) followed by the backward (dq, dk, dv).  Inputs are
 resident in HBM before the timed region starts.  One JSON line is printed:
-whole-step TFLOP/s as `value`, the forward and backward separately, a roofline
-object for the dominant kernel and the CPU oracle timed on a bounded sample.
+whole-step TFLOP/s as `value`, the forward and the two backward passes separately,
+a roofline object for the dominant kernel, the rate the matrix cores sustain on
+such data with no other work (the practical ceiling under the power limit) and
+the CPU oracle timed on a bounded sample.
 
 FLOP convention (algorithmic, strictly causal pairs only): one contraction is
 2*d FLOP per (query, key) pair with key < query; forward = 2 contractions,
-backward = 5.  Nothing else (masked halves of diagonal tiles, recomputation,
-element-wise work) is counted.
+backward = 5 (query-stationary pass: logits, dO.v, dQ = 3; key-stationary pass:
+dK, dV = 2, its recomputation of the first two is not counted).  Nothing else
+(masked halves of diagonal tiles, recomputation, element-wise work) is counted.
+
+`roofline.traffic` (HBM bytes per launch of the dominant kernel) comes from
+rocprofv3 counter runs that cannot be made from inside this script; it is read
+from profiles/hbm_traffic_B8_H16_T4096_d128.txt when that file is present.
 """
 from __future__ import annotations
 
@@ -50,6 +57,19 @@ def event_time_ms(fn, iters):
     e1.record()
     e1.synchronize()
     return e0.elapsed_time(e1) / iters
+
+
+def hbm_traffic(kernel):
+    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see the file)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_B8_H16_T4096_d128.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("JSON:"):
+                    return json.loads(line[5:]).get(kernel)
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(w, q, k, v, dout, n_heads, with_bwd):
@@ -141,16 +161,24 @@ def main():
 
     f_fwd, f_bwd = flops_fwd(B, H, T, d), flops_bwd(B, H, T, d)
     ms_fwd = event_time_ms(fwd, args.kernel_iters)
-    ms_bwd = event_time_ms(bwd, args.kernel_iters) if with_bwd else 0.0
     tf_fwd = f_fwd / (ms_fwd * 1e-3) / 1e12
-    tf_bwd = f_bwd / (ms_bwd * 1e-3) / 1e12 if with_bwd else 0.0
+    kernels = {"fwd_bf16_kernel": (ms_fwd, f_fwd)}
+    if with_bwd:
+        ms_bwd = event_time_ms(bwd, args.kernel_iters)
+        ms_dq = event_time_ms(lambda: sb.sb_attn_bwd_dq(qd, kd, vd, m, gd, dq, ws), args.kernel_iters)
+        ms_dkdv = event_time_ms(lambda: sb.sb_attn_bwd_dkdv(qd, kd, vd, gd, ws, dk, dv), args.kernel_iters)
+        tf_bwd = f_bwd / (ms_bwd * 1e-3) / 1e12
+        kernels["bwd_dq_kernel"] = (ms_dq, 0.6 * f_bwd)
+        kernels["bwd_dkv_kernel"] = (ms_dkdv, 0.4 * f_bwd)
     value = (f_fwd + (f_bwd if with_bwd else 0.0)) / (ms_per_step * 1e-3) / 1e12
 
-    # dominant kernel = the one with the larger share of the step
-    if with_bwd and ms_bwd >= ms_fwd:
-        dom, dom_tf, dom_ms = "sb_attn_bwd (bwd_bf16_kernel)", tf_bwd, ms_bwd
-    else:
-        dom, dom_tf, dom_ms = "sb_attn_fwd_train (fwd_bf16_kernel)", tf_fwd, ms_fwd
+    # the rate the matrix cores sustain on data like the workload's with nothing else running
+    mfma_tf, mfma_mhz = sb.sb_diag_mfma_rate(kd.reshape(-1)[: 1 << 21], iters=4000)
+
+    # dominant kernel = the one with the largest share of the step
+    dom = max(kernels, key=lambda n: kernels[n][0])
+    dom_ms, dom_flop = kernels[dom]
+    dom_tf = dom_flop / (dom_ms * 1e-3) / 1e12
 
     out = {
         "metric": "stick-breaking attn fwd/bwd TFLOP/s + % bf16 MFMA peak, B8 H16 T4096 d128",
@@ -169,10 +197,14 @@ def main():
                    "inputs": "iid N(0,1) bf16, heads h>=H/2 with k*3, seed 2",
                    "step": "fwd_train + bwd" if with_bwd else "fwd_train", "early_halt": "off"},
         "fwd": {"ms": ms_fwd, "tflops": tf_fwd, "frac_bf16_peak": tf_fwd / PEAK_BF16_TFLOPS},
-        "bwd": {"ms": ms_bwd, "tflops": tf_bwd, "frac_bf16_peak": tf_bwd / PEAK_BF16_TFLOPS} if with_bwd else None,
+        "bwd": {"ms": ms_bwd, "tflops": tf_bwd, "frac_bf16_peak": tf_bwd / PEAK_BF16_TFLOPS,
+                "dq_pass_ms": ms_dq, "dkdv_pass_ms": ms_dkdv} if with_bwd else None,
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": dom_tf, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": dom_tf / PEAK_BF16_TFLOPS, "avg_launch_ms": dom_ms,
-                     "traffic": None},
+                     "flop_per_launch": dom_flop, "traffic": hbm_traffic(dom)},
+        "mfma_only_ceiling": {"tflops": mfma_tf, "frac_bf16_peak": mfma_tf / PEAK_BF16_TFLOPS,
+                              "shader_clock_mhz": mfma_mhz,
+                              "what": "32x32x16 bf16 MFMAs alone, operands = the workload's k, 2 waves per SIMD"},
     }
     if args.cpu_heads > 0:
         out["cpu_baseline"] = cpu_baseline(w, q, k, v, dout, args.cpu_heads, with_bwd)

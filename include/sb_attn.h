@@ -85,6 +85,33 @@ int sb_attn_bwd(const void* q, const void* k, const void* v, const float* m, con
                 float* dq, float* dk, float* dv, void* workspace, size_t workspace_bytes,
                 int B, int H, int T, int d, void* stream);
 
+/*
+ * The two passes of sb_attn_bwd on their own (same arguments, same workspace, which
+ * carries the per-strip sums from the first to the second):
+ *   sb_attn_bwd_dq    query-stationary pass of Algorithm 2: dq, and the carries.
+ *   sb_attn_bwd_dkdv  key-stationary pass: dk, dv from the carries; must follow
+ *                     sb_attn_bwd_dq on the same inputs and workspace.
+ * sb_attn_bwd is exactly the first followed by the second.
+ */
+int sb_attn_bwd_dq(const void* q, const void* k, const void* v, const float* m, const void* dout,
+                   float* dq, void* workspace, size_t workspace_bytes,
+                   int B, int H, int T, int d, void* stream);
+int sb_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* dout,
+                     float* dk, float* dv, void* workspace, size_t workspace_bytes,
+                     int B, int H, int T, int d, void* stream);
+
+/*
+ * Measurement aid (not part of the method): runs `iters` x 16 independent
+ * 32x32x16 bf16 MFMAs per wavefront, two wavefronts per SIMD on the whole chip,
+ * on operands taken from `operands` (device, bf16, at least 1 MiB, 16-byte
+ * aligned) and nothing else.  The rate it reaches is what the matrix cores
+ * sustain on that data under the chip's power limit.  ticks (device, 3 x u64,
+ * 16-byte aligned) receives [0] shader clocks and [1] 100 MHz reference ticks of
+ * one wavefront's loop; *flop (host) receives the FLOP the launch executes.
+ */
+int sb_diag_mfma_rate(const void* operands, size_t operand_bytes, int iters, unsigned long long* ticks,
+                      double* flop, void* stream);
+
 /* Human-readable name of a status code (static storage). */
 const char* sb_status_string(int status);
 

@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libsbattn.so")
 
 EXPORTS = (
     "sb_attn_fwd", "sb_attn_fwd_train", "sb_attn_fwd_f32",
-    "sb_attn_bwd_workspace_bytes", "sb_attn_bwd",
+    "sb_attn_bwd_workspace_bytes", "sb_attn_bwd", "sb_attn_bwd_dq", "sb_attn_bwd_dkdv",
+    "sb_diag_mfma_rate",
     "sb_status_string", "sb_version",
 )
 
@@ -49,6 +50,12 @@ def load(build_if_missing: bool = True):
     lib.sb_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
     lib.sb_attn_bwd.argtypes = [vp, vp, vp, fp, vp, fp, fp, fp, vp, ctypes.c_size_t, ci, ci, ci, ci, vp]
     lib.sb_attn_bwd.restype = ci
+    lib.sb_attn_bwd_dq.argtypes = [vp, vp, vp, fp, vp, fp, vp, ctypes.c_size_t, ci, ci, ci, ci, vp]
+    lib.sb_attn_bwd_dq.restype = ci
+    lib.sb_attn_bwd_dkdv.argtypes = [vp, vp, vp, vp, fp, fp, vp, ctypes.c_size_t, ci, ci, ci, ci, vp]
+    lib.sb_attn_bwd_dkdv.restype = ci
+    lib.sb_diag_mfma_rate.argtypes = [vp, ctypes.c_size_t, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.sb_diag_mfma_rate.restype = ci
     lib.sb_status_string.argtypes = [ci]
     lib.sb_status_string.restype = ctypes.c_char_p
     lib.sb_version.argtypes = []
@@ -159,3 +166,64 @@ def sb_attn_bwd(q, k, v, m, dout, dq=None, dk=None, dv=None, workspace=None, str
                             B, H, T, d, _stream(stream))
     _check(rc, "sb_attn_bwd")
     return dq, dk, dv
+
+
+def _workspace(workspace, B, H, T, d, device):
+    need = sb_attn_bwd_workspace_bytes(B, H, T, d)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    ws_ptr = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    return workspace, ws_ptr, ws_bytes
+
+
+def sb_attn_bwd_dq(q, k, v, m, dout, dq=None, workspace=None, stream=None):
+    """Query-stationary pass of the backward.  Returns (dq, workspace)."""
+    B, H, T, d = _dims(q)
+    dq = torch.empty(q.shape, dtype=torch.float32, device=q.device) if dq is None else dq
+    workspace, ws_ptr, ws_bytes = _workspace(workspace, B, H, T, d, q.device)
+    rc = load().sb_attn_bwd_dq(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, q.shape, "k"),
+                               _ptr(v, torch.bfloat16, q.shape, "v"), _ptr(m, torch.float32, (B, H, T), "m"),
+                               _ptr(dout, torch.bfloat16, q.shape, "dout"),
+                               _ptr(dq, torch.float32, q.shape, "dq"), ws_ptr, ws_bytes,
+                               B, H, T, d, _stream(stream))
+    _check(rc, "sb_attn_bwd_dq")
+    return dq, workspace
+
+
+def sb_attn_bwd_dkdv(q, k, v, dout, workspace, dk=None, dv=None, stream=None):
+    """Key-stationary pass of the backward (after sb_attn_bwd_dq on the same workspace).  Returns (dk, dv)."""
+    B, H, T, d = _dims(q)
+    mk = lambda: torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    dk = mk() if dk is None else dk
+    dv = mk() if dv is None else dv
+    _, ws_ptr, ws_bytes = _workspace(workspace, B, H, T, d, q.device)
+    rc = load().sb_attn_bwd_dkdv(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, q.shape, "k"),
+                                 _ptr(v, torch.bfloat16, q.shape, "v"), _ptr(dout, torch.bfloat16, q.shape, "dout"),
+                                 _ptr(dk, torch.float32, q.shape, "dk"), _ptr(dv, torch.float32, q.shape, "dv"),
+                                 ws_ptr, ws_bytes, B, H, T, d, _stream(stream))
+    _check(rc, "sb_attn_bwd_dkdv")
+    return dk, dv
+
+
+def sb_diag_mfma_rate(operands, iters=2000, stream=None):
+    """MFMA-only rate on the given bf16 operand data.  Returns (TFLOP/s, shader clock in MHz)."""
+    if not operands.is_cuda or operands.dtype != torch.bfloat16 or not operands.is_contiguous():
+        raise SbAttnError("operands must be a contiguous bf16 tensor on the GPU")
+    ticks = torch.zeros(4, dtype=torch.int64, device=operands.device)
+    flop = ctypes.c_double(0.0)
+    nbytes = operands.numel() * 2
+    run = lambda: _check(load().sb_diag_mfma_rate(ctypes.c_void_p(operands.data_ptr()), nbytes, int(iters),
+                                                  ctypes.c_void_p(ticks.data_ptr()), ctypes.byref(flop),
+                                                  _stream(stream)), "sb_diag_mfma_rate")
+    run()
+    s = torch.cuda.current_stream() if stream is None else stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(s)
+    run()
+    e1.record(s)
+    e1.synchronize()
+    ms = e0.elapsed_time(e1)
+    t = ticks.cpu().tolist()
+    mhz = t[0] / (t[1] / 100e6) / 1e6 if t[1] > 0 else float("nan")
+    return flop.value / (ms * 1e-3) / 1e12, mhz

@@ -65,11 +65,17 @@ size_t sb_attn_bwd_workspace_bytes(int B, int H, int T, int d)
     return sb::bwd_workspace_bytes(B, H, T);
 }
 
-int sb_attn_bwd(const void* q, const void* k, const void* v, const float* m, const void* dout,
+}  // extern "C"
+
+namespace {
+
+int bwd_checked(const void* q, const void* k, const void* v, const float* m, const void* dout,
                 float* dq, float* dk, float* dv, void* workspace, size_t workspace_bytes,
-                int B, int H, int T, int d, void* stream)
+                int B, int H, int T, int d, int passes, void* stream)
 {
-    if (!q || !k || !v || !m || !dout || !dq || !dk || !dv) return SB_ERR_NULL;
+    if (!q || !k || !v || !dout) return SB_ERR_NULL;
+    if ((passes & 1) && (!m || !dq)) return SB_ERR_NULL;
+    if ((passes & 2) && (!dk || !dv)) return SB_ERR_NULL;
     if (int rc = check_shape(B, H, T, d)) return rc;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(m) || !aligned16(dout) ||
         !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
@@ -79,7 +85,43 @@ int sb_attn_bwd(const void* q, const void* k, const void* v, const float* m, con
                                        static_cast<const uint16_t*>(v), m,
                                        static_cast<const uint16_t*>(dout), dq, dk, dv,
                                        static_cast<float*>(workspace),
-                                       B, H, T, d, static_cast<hipStream_t>(stream));
+                                       B, H, T, d, passes, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sb_attn_bwd(const void* q, const void* k, const void* v, const float* m, const void* dout,
+                float* dq, float* dk, float* dv, void* workspace, size_t workspace_bytes,
+                int B, int H, int T, int d, void* stream)
+{
+    return bwd_checked(q, k, v, m, dout, dq, dk, dv, workspace, workspace_bytes, B, H, T, d, 3, stream);
+}
+
+int sb_attn_bwd_dq(const void* q, const void* k, const void* v, const float* m, const void* dout,
+                   float* dq, void* workspace, size_t workspace_bytes,
+                   int B, int H, int T, int d, void* stream)
+{
+    return bwd_checked(q, k, v, m, dout, dq, nullptr, nullptr, workspace, workspace_bytes, B, H, T, d, 1, stream);
+}
+
+int sb_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* dout,
+                     float* dk, float* dv, void* workspace, size_t workspace_bytes,
+                     int B, int H, int T, int d, void* stream)
+{
+    return bwd_checked(q, k, v, nullptr, dout, nullptr, dk, dv, workspace, workspace_bytes, B, H, T, d, 2, stream);
+}
+
+int sb_diag_mfma_rate(const void* operands, size_t operand_bytes, int iters, unsigned long long* ticks,
+                      double* flop, void* stream)
+{
+    if (!operands || !ticks || !flop) return SB_ERR_NULL;
+    if (operand_bytes < (1u << 20) || iters < 1) return SB_ERR_SHAPE;
+    if (!aligned16(operands) || !aligned16(ticks)) return SB_ERR_ALIGN;
+    *flop = sb::diag_mfma_flop(iters);
+    hipError_t e = sb::launch_diag_mfma(operands, iters, ticks, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
 }
 

@@ -705,7 +705,7 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 template <int D>
 hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, const float* m,
                       const uint16_t* dout, float* dq, float* dk, float* dv, float* workspace,
-                      int BH, int T, hipStream_t stream)
+                      int BH, int T, int passes, hipStream_t stream)
 {
     const int nt32 = (T + 31) / 32;
     const int nqb = (T + BQ - 1) / BQ;
@@ -717,19 +717,24 @@ hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, c
     const long bq = 8L * ((BH + 7) / 8) * ((nqb + 1) / 2);
     const long bk = 8L * ((BH + 7) / 8) * ((nkb + 1) / 2);
     if (bq > 0x7fffffffL || bk > 0x7fffffffL) return hipErrorInvalidValue;
-    hipError_t e;
-    hipLaunchKernelGGL((bwd_dq_kernel<D, false>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
-                       q, k, v, m, dout, dq, ca, cb, fq, T, BH, nqb, nt32);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_dq_kernel<D, true>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
-                       q, k, v, m, dout, dq, ca, cb, fq, T, BH, nqb, nt32);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_dkv_kernel<D, false>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
-                       q, k, v, dout, ca, cb, dk, dv, fk, T, BH, nkb, nt32);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_dkv_kernel<D, true>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
-                       q, k, v, dout, ca, cb, dk, dv, fk, T, BH, nkb, nt32);
-    return hipGetLastError();
+    hipError_t e = hipSuccess;
+    if (passes & 1) {
+        hipLaunchKernelGGL((bwd_dq_kernel<D, false>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
+                           q, k, v, m, dout, dq, ca, cb, fq, T, BH, nqb, nt32);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        hipLaunchKernelGGL((bwd_dq_kernel<D, true>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
+                           q, k, v, m, dout, dq, ca, cb, fq, T, BH, nqb, nt32);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (passes & 2) {
+        hipLaunchKernelGGL((bwd_dkv_kernel<D, false>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
+                           q, k, v, dout, ca, cb, dk, dv, fk, T, BH, nkb, nt32);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        hipLaunchKernelGGL((bwd_dkv_kernel<D, true>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
+                           q, k, v, dout, ca, cb, dk, dv, fk, T, BH, nkb, nt32);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 }  // namespace
@@ -743,11 +748,11 @@ size_t bwd_workspace_bytes(int B, int H, int T)
 
 hipError_t launch_bwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const float* m,
                            const uint16_t* dout, float* dq, float* dk, float* dv, float* workspace,
-                           int B, int H, int T, int d, hipStream_t stream)
+                           int B, int H, int T, int d, int passes, hipStream_t stream)
 {
     const int BH = B * H;
-    if (d == 64) return launch_one<64>(q, k, v, m, dout, dq, dk, dv, workspace, BH, T, stream);
-    return launch_one<128>(q, k, v, m, dout, dq, dk, dv, workspace, BH, T, stream);
+    if (d == 64) return launch_one<64>(q, k, v, m, dout, dq, dk, dv, workspace, BH, T, passes, stream);
+    return launch_one<128>(q, k, v, m, dout, dq, dk, dv, workspace, BH, T, passes, stream);
 }
 
 }  // namespace sb

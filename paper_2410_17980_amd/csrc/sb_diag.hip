@@ -1,0 +1,63 @@
+// Diagnostic kernel: what the matrix cores sustain on given operand data with no
+// other work in flight.  The published peak (2.5 PFLOP/s dense bf16) assumes the
+// nominal 2.4 GHz clock; with operands that toggle like real data the chip lowers
+// its clock under the power limit, and the rate this kernel reaches is the ceiling
+// any kernel built on the same MFMA instruction can approach on the same data.
+#include "sb_kernels.h"
+#include "sb_mma.h"
+
+namespace sb {
+namespace {
+
+constexpr int DIAG_WGS = 512;          // two workgroups of 4 waves per CU: 2 waves per SIMD
+constexpr int DIAG_MFMA_PER_ITER = 16;
+
+__global__ void __launch_bounds__(256, 2)
+diag_mfma_kernel(const u32x4* __restrict__ data, int iters, unsigned long long* __restrict__ ticks)
+{
+    const int tid = threadIdx.x + blockIdx.x * 256;
+    bf16x8 a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i] = __builtin_bit_cast(bf16x8, data[(tid * 8 + i) & 0xffff]);
+        b[i] = __builtin_bit_cast(bf16x8, data[(tid * 8 + 4 + i) & 0xffff]);
+    }
+    f32x16 c[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) c[j][r] = 0.0f;
+    const long long t0 = clock64(), w0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[(i + j) & 3], c[j], 0, 0, 0);
+    }
+    const long long t1 = clock64(), w1 = wall_clock64();
+    float s = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) s += c[j][0];
+    if (s == 12345.678f) ticks[2] = 1;                  // keeps the products alive
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        ticks[0] = (unsigned long long)(t1 - t0);       // shader clocks
+        ticks[1] = (unsigned long long)(w1 - w0);       // 100 MHz reference ticks
+    }
+}
+
+}  // namespace
+
+hipError_t launch_diag_mfma(const void* operands, int iters, unsigned long long* ticks, hipStream_t stream)
+{
+    hipLaunchKernelGGL(diag_mfma_kernel, dim3(DIAG_WGS), dim3(256), 0, stream,
+                       static_cast<const u32x4*>(operands), iters, ticks);
+    return hipGetLastError();
+}
+
+double diag_mfma_flop(int iters)
+{
+    return (double)DIAG_WGS * 4.0 * iters * DIAG_MFMA_PER_ITER * (2.0 * 32 * 32 * 16);
+}
+
+}  // namespace sb

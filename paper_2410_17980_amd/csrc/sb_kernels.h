@@ -15,10 +15,16 @@ hipError_t launch_fwd_f32(const float* q, const float* k, const float* v, float*
 hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o,
                            float* m, int B, int H, int T, int d, hipStream_t stream);
 
-// workspace: bwd_workspace_bytes(B, H, T) bytes of device memory, 16-byte aligned
+// workspace: bwd_workspace_bytes(B, H, T) bytes of device memory, 16-byte aligned.
+// passes: bit 0 = query-stationary pass (dq and the carries in the workspace),
+// bit 1 = key-stationary pass (dk, dv from the carries).
 size_t bwd_workspace_bytes(int B, int H, int T);
 hipError_t launch_bwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const float* m,
                            const uint16_t* dout, float* dq, float* dk, float* dv, float* workspace,
-                           int B, int H, int T, int d, hipStream_t stream);
+                           int B, int H, int T, int d, int passes, hipStream_t stream);
+
+// MFMA-only diagnostic: operands = at least 1 MiB of bf16 on the device, ticks = 3 x u64 on the device
+hipError_t launch_diag_mfma(const void* operands, int iters, unsigned long long* ticks, hipStream_t stream);
+double diag_mfma_flop(int iters);
 
 }  // namespace sb

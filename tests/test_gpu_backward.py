@@ -124,3 +124,28 @@ def test_workload_4_sampled_heads(sb, oracle, gen):
             print(f"{name}[{b},{h}]: err {err:.3e} max|ref| {np.abs(r).max():.3e}")
             assert err <= grad_tol(r), f"{name}[{b},{h}]: {err} (max |ref| {np.abs(r).max()})"
     assert torch.isfinite(dq).all() and torch.isfinite(dk).all() and torch.isfinite(dv).all()
+
+
+def test_bwd_split_passes_equal_the_whole(sb, gen):
+    """sb_attn_bwd_dq followed by sb_attn_bwd_dkdv on one workspace is sb_attn_bwd, bit for bit."""
+    q, k, v, g = dev(*gen.gaussian(2, 3, 333, 128, seed=21, dtype="bf16", with_dout=True))
+    o, m = sb.sb_attn_fwd_train(q, k, v)
+    dq, dk, dv = sb.sb_attn_bwd(q, k, v, m, g)
+    dq2, ws = sb.sb_attn_bwd_dq(q, k, v, m, g)
+    dk2, dv2 = sb.sb_attn_bwd_dkdv(q, k, v, g, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dq, dq2) and torch.equal(dk, dk2) and torch.equal(dv, dv2)
+
+
+def test_bwd_sharp_blocks_are_redone_only_where_needed(sb, oracle, gen):
+    """One head with logits far beyond the linear-domain range next to an ordinary one:
+    the flagged blocks go through the log-domain variant, the rest do not, and both match."""
+    q, k, v, g = gen.gaussian(1, 2, 400, 128, seed=22, dtype="bf16", with_dout=True)
+    k[:, 1] = (k[:, 1].float() * 40.0).to(k.dtype)
+    check(sb, oracle, q, k, v, g)
+
+
+def test_mfma_rate_diagnostic_runs(sb):
+    x = torch.randn(1 << 20, device="cuda").to(torch.bfloat16)
+    tf, mhz = sb.sb_diag_mfma_rate(x, iters=200)
+    assert 100.0 < tf < 2600.0 and 500.0 < mhz < 2600.0
