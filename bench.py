@@ -111,6 +111,9 @@ def main():
     ap.add_argument("--kernel-iters", type=int, default=20, help="launches per kernel for the event timing")
     ap.add_argument("--passes", choices=["fwd", "fwd+bwd"], default=DEFAULT_PASSES,
                     help="what one step runs")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB element-wise copy kernel (3 times): the known traffic the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (batch and heads shard "
@@ -143,6 +146,14 @@ def main():
         sb.sb_attn_bwd(qd, kd, vd, m, gd, dq, dk, dv, ws)
 
     with_bwd = args.passes == "fwd+bwd"
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.bitwise_or(src, 0, out=dst)      # a kernel (a plain copy_ may go through the DMA engines)
+        torch.cuda.synchronize()
+        del src, dst
 
     def step():
         fwd()
