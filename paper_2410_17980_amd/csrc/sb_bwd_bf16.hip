@@ -636,8 +636,8 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             for (int u = 0; u < 2; ++u) {
                 const int j = jt * TK + 32 * u + n;
                 // rows past T: an infinite carry gives A = 0 and G = 0, and with cb = 0 also dZ = 0
-                cn[u][0] = (j < T) ? cag[j] : INFINITY;
-                cn[u][1] = (j < T) ? cbg[j] : 0.0f;
+                cn[u][0] = (j < T && wave_live) ? cag[j] : INFINITY;   // a dead wave's rows lie outside the arrays
+                cn[u][1] = (j < T && wave_live) ? cbg[j] : 0.0f;
             }
         };
         if (ntile > 0) {
