@@ -183,6 +183,14 @@ def main():
         kernels["bwd_dkv_kernel"] = (ms_dkdv, 0.4 * f_bwd)
     value = (f_fwd + (f_bwd if with_bwd else 0.0)) / (ms_per_step * 1e-3) / 1e12
 
+    # early halt (inference forward; NOT part of the step or of `value`): how much of the sweep
+    # the workload's data lets a block skip at eps = 1e-9, and what that buys
+    counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+    sb.sb_attn_fwd_halt(qd, kd, vd, 1e-9, o, counts)
+    swept, full = counts.cpu().tolist()
+    ms_inf = event_time_ms(lambda: sb.sb_attn_fwd(qd, kd, vd, o), args.kernel_iters)
+    ms_halt = event_time_ms(lambda: sb.sb_attn_fwd_halt(qd, kd, vd, 1e-9, o), args.kernel_iters)
+
     # the rate the matrix cores sustain on data like the workload's with nothing else running
     mfma_tf, mfma_mhz = sb.sb_diag_mfma_rate(kd.reshape(-1)[: 1 << 21], iters=4000)
 
@@ -213,6 +221,10 @@ def main():
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": dom_tf, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": dom_tf / PEAK_BF16_TFLOPS, "avg_launch_ms": dom_ms,
                      "flop_per_launch": dom_flop, "traffic": hbm_traffic(dom)},
+        "early_halt": {"eps": 1e-9, "ms_full_sweep": ms_inf, "ms_halted": ms_halt, "speedup": ms_inf / ms_halt,
+                       "tiles_swept_frac": swept / max(full, 1),
+                       "note": "sb_attn_fwd_halt vs sb_attn_fwd (forward without m); depends on the data: "
+                               "N(0,1) logits exhaust the stick within a few dozen keys"},
         "mfma_only_ceiling": {"tflops": mfma_tf, "frac_bf16_peak": mfma_tf / PEAK_BF16_TFLOPS,
                               "shader_clock_mhz": mfma_mhz,
                               "what": "32x32x16 bf16 MFMAs alone, operands = the workload's k, 2 waves per SIMD"},

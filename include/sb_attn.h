@@ -53,6 +53,21 @@ int sb_attn_fwd(const void* q, const void* k, const void* v, void* o,
                 int B, int H, int T, int d, void* stream);
 
 /*
+ * Inference forward with early halt (the paper's "conditional computation",
+ * section 4.1): as sb_attn_fwd, but a block of 128 query rows stops sweeping keys
+ * once every one of its rows has less than eps of its stick left
+ * (prod (1 - beta) < eps over the keys swept so far).  No skipped key can weigh more
+ * than what is left, so |o_j - exact o_j| <= eps * max_i |v_i| per component.
+ * 0 < eps < 1 (SB_ERR_SHAPE otherwise).  How much is skipped depends on the data.
+ * tile_counts: optional (may be NULL) device pointer to 2 x u64, 16-byte aligned;
+ * the call ADDS to [0] the 64-key tiles swept beyond the diagonal band and to [1]
+ * the tiles a full sweep would take (per 128-row block), for reporting.
+ */
+int sb_attn_fwd_halt(const void* q, const void* k, const void* v, void* o,
+                     float eps, unsigned long long* tile_counts,
+                     int B, int H, int T, int d, void* stream);
+
+/*
  * Training forward: as sb_attn_fwd, and also writes m[b,h,j] (fp32) =
  * -sum_{i<j} softplus(z[i,j]) = log(1 - sum_i A[i,j]), the vector that
  * Algorithm 1 stores at its end and Algorithm 2 reads back.  m[.,.,0] = 0.

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsbattn.so")
 
 EXPORTS = (
-    "sb_attn_fwd", "sb_attn_fwd_train", "sb_attn_fwd_f32",
+    "sb_attn_fwd", "sb_attn_fwd_halt", "sb_attn_fwd_train", "sb_attn_fwd_f32",
     "sb_attn_bwd_workspace_bytes", "sb_attn_bwd", "sb_attn_bwd_dq", "sb_attn_bwd_dkdv",
     "sb_diag_mfma_rate",
     "sb_status_string", "sb_version",
@@ -42,6 +42,8 @@ def load(build_if_missing: bool = True):
     vp, ci, fp = ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p
     lib.sb_attn_fwd.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, vp]
     lib.sb_attn_fwd.restype = ci
+    lib.sb_attn_fwd_halt.argtypes = [vp, vp, vp, vp, ctypes.c_float, vp, ci, ci, ci, ci, vp]
+    lib.sb_attn_fwd_halt.restype = ci
     lib.sb_attn_fwd_train.argtypes = [vp, vp, vp, vp, fp, ci, ci, ci, ci, vp]
     lib.sb_attn_fwd_train.restype = ci
     lib.sb_attn_fwd_f32.argtypes = [fp, fp, fp, fp, fp, ci, ci, ci, ci, vp]
@@ -111,6 +113,19 @@ def sb_attn_fwd(q, k, v, o=None, stream=None):
                             _ptr(v, torch.bfloat16, q.shape, "v"), _ptr(o, torch.bfloat16, q.shape, "o"),
                             B, H, T, d, _stream(stream))
     _check(rc, "sb_attn_fwd")
+    return o
+
+
+def sb_attn_fwd_halt(q, k, v, eps, o=None, tile_counts=None, stream=None):
+    """bf16 forward with early halt.  tile_counts: optional int64 tensor of 2 on the GPU (added to)."""
+    B, H, T, d = _dims(q)
+    if o is None:
+        o = torch.empty_like(q)
+    tc = _ptr(tile_counts, torch.int64, (2,), "tile_counts") if tile_counts is not None else None
+    rc = load().sb_attn_fwd_halt(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, q.shape, "k"),
+                                 _ptr(v, torch.bfloat16, q.shape, "v"), _ptr(o, torch.bfloat16, q.shape, "o"),
+                                 ctypes.c_float(eps), tc, B, H, T, d, _stream(stream))
+    _check(rc, "sb_attn_fwd_halt")
     return o
 
 

@@ -35,6 +35,21 @@ int sb_attn_fwd(const void* q, const void* k, const void* v, void* o,
     return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
 }
 
+int sb_attn_fwd_halt(const void* q, const void* k, const void* v, void* o,
+                     float eps, unsigned long long* tile_counts,
+                     int B, int H, int T, int d, void* stream)
+{
+    if (!q || !k || !v || !o) return SB_ERR_NULL;
+    if (int rc = check_shape(B, H, T, d)) return rc;
+    if (!(eps > 0.0f && eps < 1.0f)) return SB_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(tile_counts))
+        return SB_ERR_ALIGN;
+    hipError_t e = sb::launch_fwd_bf16_halt(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                                            static_cast<const uint16_t*>(v), static_cast<uint16_t*>(o),
+                                            eps, tile_counts, B, H, T, d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
 int sb_attn_fwd_train(const void* q, const void* k, const void* v, void* o, float* m,
                       int B, int H, int T, int d, void* stream)
 {

@@ -34,6 +34,11 @@
 // running sum).  That costs one exponential and four multiply/adds per weight; the
 // log form of Eq. 2/3 needs three transcendentals.  Where the in-lane product could
 // overflow, the wave falls back to the log form for that subtile (see ew()).
+//
+// Early halt (HALT variant, inference forward without m; the paper's "conditional
+// computation", section 4.1): the carry of a row is -log2 of the stick it has left, and
+// no weight of a farther key can exceed that.  Once every row of a query block has less
+// than eps left, the block stops sweeping: the error of o_j is at most eps * max|v|.
 #include <type_traits>
 
 #include "sb_kernels.h"
@@ -58,15 +63,17 @@ template <int D> struct FwdCfg {
 
 template <bool B> using bc = std::integral_constant<bool, B>;
 
-template <int D, bool WRITE_M>
+template <int D, bool WRITE_M, bool HALT>
 __global__ void __launch_bounds__(64 * NW, 2)
 fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                 const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ m,
-                int T, int BH, int nqb)
+                int T, int BH, int nqb, float halt_carry, unsigned long long* __restrict__ tile_counts)
 {
     using C = FwdCfg<D>;
     constexpr int NPW = C::NPW;
+    static_assert(!(HALT && WRITE_M), "a halted sweep does not know m");
     __shared__ __attribute__((aligned(1024))) char smem[NS * C::STAGE];
+    __shared__ int s_halt[2][NW];                       // per iteration parity and wave: all rows exhausted
 
     // workgroup -> (head, pair of query blocks).  Consecutive workgroup ids go round
     // the 8 XCDs, so every XCD gets its own heads and K/V of a head stay in one L2.
@@ -321,9 +328,29 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                 }
             }
         }
+        if constexpr (HALT) {
+            if (lane == 0) { s_halt[0][wave] = 0; s_halt[1][wave] = 0; }   // read only after later barriers
+        }
         for (; it < ntile; ++it) {                           // tiles fully visible to every row
             const char* sp = begin_iter(it);
+            if constexpr (HALT) {
+                // flags of the previous iteration, written before the barrier just passed; all
+                // waves read the same four words, so they leave the loop together
+                const int* f = s_halt[(it + 1) & 1];
+                if (it > ndiag && (f[0] & f[1] & f[2] & f[3])) break;
+            }
             hot_tile(sp);
+            if constexpr (HALT) {
+                // both half-waves hold the same carry; rows past T repeat row T-1
+                const int done = __builtin_amdgcn_ballot_w64(a < halt_carry) == 0;
+                if (lane == 0) s_halt[it & 1][wave] = done;
+            }
+        }
+        if constexpr (HALT) {
+            if (tile_counts && tid == 0) {
+                atomicAdd(&tile_counts[0], (unsigned long long)it);        // tiles swept
+                atomicAdd(&tile_counts[1], (unsigned long long)ntile);     // tiles of the full sweep
+            }
         }
         dma_wait<0>();                                       // the trailing re-load
 
@@ -347,15 +374,15 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     }
 }
 
-template <int D, bool WRITE_M>
+template <int D, bool WRITE_M, bool HALT>
 hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o, float* m,
-                      int BH, int T, hipStream_t stream)
+                      int BH, int T, float halt_carry, unsigned long long* tile_counts, hipStream_t stream)
 {
     const int nqb = (T + BQ - 1) / BQ;
     const long blocks = 8L * ((BH + 7) / 8) * ((nqb + 1) / 2);
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((fwd_bf16_kernel<D, WRITE_M>), dim3((unsigned)blocks), dim3(64 * NW), 0, stream,
-                       q, k, v, o, m, T, BH, nqb);
+    hipLaunchKernelGGL((fwd_bf16_kernel<D, WRITE_M, HALT>), dim3((unsigned)blocks), dim3(64 * NW), 0, stream,
+                       q, k, v, o, m, T, BH, nqb, halt_carry, tile_counts);
     return hipGetLastError();
 }
 
@@ -366,10 +393,20 @@ hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t*
 {
     const int BH = B * H;
     if (d == 64)
-        return m ? launch_one<64, true>(q, k, v, o, m, BH, T, stream)
-                 : launch_one<64, false>(q, k, v, o, m, BH, T, stream);
-    return m ? launch_one<128, true>(q, k, v, o, m, BH, T, stream)
-             : launch_one<128, false>(q, k, v, o, m, BH, T, stream);
+        return m ? launch_one<64, true, false>(q, k, v, o, m, BH, T, 0.0f, nullptr, stream)
+                 : launch_one<64, false, false>(q, k, v, o, m, BH, T, 0.0f, nullptr, stream);
+    return m ? launch_one<128, true, false>(q, k, v, o, m, BH, T, 0.0f, nullptr, stream)
+             : launch_one<128, false, false>(q, k, v, o, m, BH, T, 0.0f, nullptr, stream);
+}
+
+hipError_t launch_fwd_bf16_halt(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o,
+                                float eps, unsigned long long* tile_counts,
+                                int B, int H, int T, int d, hipStream_t stream)
+{
+    const int BH = B * H;
+    const float halt_carry = -log2f(eps);               // carry = -log2(stick left)
+    if (d == 64) return launch_one<64, false, true>(q, k, v, o, nullptr, BH, T, halt_carry, tile_counts, stream);
+    return launch_one<128, false, true>(q, k, v, o, nullptr, BH, T, halt_carry, tile_counts, stream);
 }
 
 }  // namespace sb

@@ -15,6 +15,11 @@ hipError_t launch_fwd_f32(const float* q, const float* k, const float* v, float*
 hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o,
                            float* m, int B, int H, int T, int d, hipStream_t stream);
 
+// forward that stops sweeping a query block once every row has less than eps of its stick left
+hipError_t launch_fwd_bf16_halt(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o,
+                                float eps, unsigned long long* tile_counts,
+                                int B, int H, int T, int d, hipStream_t stream);
+
 // workspace: bwd_workspace_bytes(B, H, T) bytes of device memory, 16-byte aligned.
 // passes: bit 0 = query-stationary pass (dq and the carries in the workspace),
 // bit 1 = key-stationary pass (dk, dv from the carries).

@@ -178,3 +178,57 @@ def test_workload_5_long_context_tail_rows(sb, oracle, gen):
     for b, h in gen.slice_picks(w, 2):
         ref, _ = oracle.fwd(to64(q[b, h]), to64(k[b, h]), to64(v[b, h]), rows=(r0, r1))
         assert max_abs(to64(o[b, h, r0:r1]), ref) <= BF16_TOL
+
+
+# ---------------------------------------------------------------- early halt (inference forward)
+def test_halt_matches_oracle_and_skips_tiles(sb, oracle, gen):
+    """N(0,1) logits use up the stick within a few dozen keys: almost every tile beyond the
+    diagonal band is skipped, and the output still matches the oracle."""
+    q, k, v = gen.gaussian(1, 3, 2048, 128, seed=31, dtype="bf16")
+    qd, kd, vd = dev(q, k, v)
+    counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+    o = sb.sb_attn_fwd_halt(qd, kd, vd, 1e-9, tile_counts=counts)
+    torch.cuda.synchronize()
+    ref, _ = oracle.fwd(to64(q), to64(k), to64(v))
+    assert max_abs(to64(o), ref) <= BF16_TOL
+    swept, full = counts.cpu().tolist()
+    print(f"tiles swept {swept} of {full}")
+    assert 0 < swept < 0.35 * full
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_halt_never_triggers_on_slowly_decaying_weights(sb, gen, d):
+    """Constant small logit: the stick is far from used up at T = 700, nothing may be skipped
+    and the result is bit-identical to the plain forward."""
+    kval = -48.0 if d == 64 else -64.0
+    q, k, v = dev(*gen.constant_logit(1, 2, 700, d, seed=32, kval=kval, dtype="bf16"))
+    counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+    o1 = sb.sb_attn_fwd(q, k, v)
+    o2 = sb.sb_attn_fwd_halt(q, k, v, 1e-6, tile_counts=counts)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
+    swept, full = counts.cpu().tolist()
+    assert swept == full > 0
+
+
+def test_halt_error_is_bounded_by_eps(sb, gen):
+    """Logits around -3: weights spread over ~100 keys.  With a coarse eps the halted result
+    differs from the full sweep by at most eps * max|v| (plus one bf16 rounding of o)."""
+    q, k, v = dev(*gen.biased_gaussian(1, 2, 1500, 128, seed=33, shift=-3.0, dtype="bf16"))
+    eps = 1e-2
+    counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+    o_full = sb.sb_attn_fwd(q, k, v).float()
+    o_halt = sb.sb_attn_fwd_halt(q, k, v, eps, tile_counts=counts).float()
+    torch.cuda.synchronize()
+    bound = eps * float(v.float().abs().max()) + 2.0 ** -7 * float(o_full.abs().max())
+    diff = float((o_full - o_halt).abs().max())
+    swept, full = counts.cpu().tolist()
+    print(f"max diff {diff:.3e} bound {bound:.3e}, tiles swept {swept} of {full}")
+    assert diff <= bound and swept < full
+
+
+def test_halt_rejects_bad_eps(sb, gen):
+    q, k, v = dev(*gen.gaussian(1, 1, 64, 64, seed=34, dtype="bf16"))
+    for eps in (0.0, 1.0, -1.0, float("nan")):
+        with pytest.raises(sb.SbAttnError):
+            sb.sb_attn_fwd_halt(q, k, v, eps)
