@@ -25,6 +25,16 @@
  *     dQ_j = s * sum_i dZ[i,j] k_i,  dK_i = s * sum_j dZ[i,j] q_j,
  *     dV_i = sum_j A[i,j] dO_j,      s = 1/sqrt(d_head)
  *
+ * Remainder bias (Appendix C, the remainder-bias output equation): with one embedding
+ * r per head, o_j gets the unused part of the stick times r,
+ *
+ *     o_j = sum_{i<j} A[i,j] v_i + rem_j r,   rem_j = 1 - sum_i A[i,j] = prod_{k<j} (1 - beta[k,j]).
+ *
+ * Its gradients follow from d rem_j / d z[i,j] = -beta[i,j] rem_j (each factor of the
+ * product depends on one logit):  dr = sum_j rem_j dO_j (over every batch entry of the
+ * head), and dZ[i,j] gains -beta[i,j] rem_j (dO_j . r): the remainder behaves like one
+ * more term in front of the cumulative sum of G.
+ *
  * Indices here are 0-based: query row j attends to keys 0..j-1.
  * Layout of every tensor: [B, H, T, d] contiguous, d fastest.  All host memory,
  * owned by the caller.  Threads: OpenMP over (head, row).
@@ -114,8 +124,9 @@ int sb_oracle_weights(const double *q, const double *k, int T, int d,
  * o   [B,H,T,d]: rows in the range are written, others untouched.
  * rem [B,H,T]  : remaining stick prod_{k<j}(1-beta[k,j]) = 1 - sum_i A[i,j];
  *                may be NULL.
+ * r   [H,d]    : remainder-bias embeddings, or NULL for plain Eq. 1.
  */
-int sb_oracle_fwd(const double *q, const double *k, const double *v,
+int sb_oracle_fwd(const double *q, const double *k, const double *v, const double *r,
                   double *o, double *rem,
                   int B, int H, int T, int d, int row_begin, int row_end)
 {
@@ -142,14 +153,18 @@ int sb_oracle_fwd(const double *q, const double *k, const double *v,
             const double *K = k + (size_t)bh * T * d;
             const double *V = v + (size_t)bh * T * d;
             double *oj = o + ((size_t)bh * T + j) * d;
-            double r = sb_row(Q + (size_t)j * d, K, j, d, A, NULL);
+            double stick = sb_row(Q + (size_t)j * d, K, j, d, A, NULL);
             for (int c = 0; c < d; ++c) oj[c] = 0.0;
             for (int i = 0; i < j; ++i) {
                 const double a = A[i];
                 const double *vi = V + (size_t)i * d;
                 for (int c = 0; c < d; ++c) oj[c] += a * vi[c];
             }
-            if (rem) rem[(size_t)bh * T + j] = r;
+            if (r) {
+                const double *rh = r + (size_t)(bh % H) * d;
+                for (int c = 0; c < d; ++c) oj[c] += stick * rh[c];
+            }
+            if (rem) rem[(size_t)bh * T + j] = stick;
         }
         free(A);
     }
@@ -159,13 +174,16 @@ int sb_oracle_fwd(const double *q, const double *k, const double *v,
 /*
  * Backward: all rows of every (b,h).  dq, dk, dv [B,H,T,d] are overwritten.
  * Works head by head with dense T x T scratch for A and dZ (16*T*T bytes).
+ * r [H,d] and dr [H,d] (overwritten): remainder bias, both NULL for plain Eq. 1.
  */
-int sb_oracle_bwd(const double *q, const double *k, const double *v,
-                  const double *dout, double *dq, double *dk, double *dv,
+int sb_oracle_bwd(const double *q, const double *k, const double *v, const double *r,
+                  const double *dout, double *dq, double *dk, double *dv, double *dr,
                   int B, int H, int T, int d)
 {
     if (!q || !k || !v || !dout || !dq || !dk || !dv) return -1;
+    if ((r == NULL) != (dr == NULL)) return -1;
     if (B < 1 || H < 1 || T < 1 || d < 1) return -2;
+    if (dr) memset(dr, 0, sizeof(double) * (size_t)H * d);
     const double scale = 1.0 / sqrt((double)d);
     double *Amat = (double *)malloc(sizeof(double) * (size_t)T * T);
     double *Zmat = (double *)malloc(sizeof(double) * (size_t)T * T);
@@ -195,8 +213,16 @@ int sb_oracle_bwd(const double *q, const double *k, const double *v,
                 int j = T - 1 - jj;
                 double *A = Amat + (size_t)j * T;
                 double *dZ = Zmat + (size_t)j * T;
-                sb_row(Q + (size_t)j * d, K, j, d, A, beta);
-                double prefix = 0.0; /* sum_{i'<=i} G[i',j] */
+                const double stick = sb_row(Q + (size_t)j * d, K, j, d, A, beta);
+                /* sum_{i'<=i} G[i',j]; with a remainder bias the unused stick comes first */
+                double prefix = r ? stick * sb_dot(DO + (size_t)j * d, r + (size_t)(bh % H) * d, d) : 0.0;
+                if (dr) {
+                    double *drh = dr + (size_t)(bh % H) * d;
+                    for (int c = 0; c < d; ++c) {
+#pragma omp atomic
+                        drh[c] += stick * DO[(size_t)j * d + c];
+                    }
+                }
                 for (int i = 0; i < j; ++i) {
                     double g = A[i] * sb_dot(DO + (size_t)j * d, V + (size_t)i * d, d);
                     prefix += g;

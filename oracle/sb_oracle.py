@@ -40,9 +40,9 @@ def _load():
         lib.sb_oracle_num_threads.restype = ci
         lib.sb_oracle_weights.argtypes = [dp, dp, ci, ci, dp, dp, dp]
         lib.sb_oracle_weights.restype = ci
-        lib.sb_oracle_fwd.argtypes = [dp, dp, dp, dp, dp, ci, ci, ci, ci, ci, ci]
+        lib.sb_oracle_fwd.argtypes = [dp, dp, dp, dp, dp, dp, ci, ci, ci, ci, ci, ci]
         lib.sb_oracle_fwd.restype = ci
-        lib.sb_oracle_bwd.argtypes = [dp, dp, dp, dp, dp, dp, dp, ci, ci, ci, ci]
+        lib.sb_oracle_bwd.argtypes = [dp, dp, dp, dp, dp, dp, dp, dp, dp, ci, ci, ci, ci]
         lib.sb_oracle_bwd.restype = ci
         _lib = lib
     return _lib
@@ -81,16 +81,25 @@ def weights(q, k):
     return A, beta, rem
 
 
-def fwd(q, k, v, rows=None):
+def _as_r(r, H, d):
+    if r is None:
+        return None
+    r = np.ascontiguousarray(np.asarray(r, dtype=np.float64)).reshape(H, d)
+    return r
+
+
+def fwd(q, k, v, rows=None, r=None):
     """Forward.  Returns (o, rem) with the input's leading shape; with
-    rows=(r0, r1) only query rows r0 <= j < r1 are computed and returned."""
+    rows=(r0, r1) only query rows r0 <= j < r1 are computed and returned.
+    r ([H,d], or [d] for one head): remainder-bias embeddings (Appendix C)."""
     shape = np.asarray(q).shape
     q4, k4, v4 = _as4(q), _as4(k), _as4(v)
     B, H, T, d = q4.shape
     r0, r1 = (0, T) if rows is None else rows
     o = np.zeros((B, H, T, d))
     rem = np.ones((B, H, T))
-    rc = _load().sb_oracle_fwd(_p(q4), _p(k4), _p(v4), _p(o), _p(rem), B, H, T, d, r0, r1)
+    rr = _as_r(r, H, d)
+    rc = _load().sb_oracle_fwd(_p(q4), _p(k4), _p(v4), _p(rr), _p(o), _p(rem), B, H, T, d, r0, r1)
     if rc != 0:
         raise RuntimeError(f"sb_oracle_fwd failed: {rc}")
     o = o[:, :, r0:r1].reshape(shape[:-2] + (r1 - r0, d))
@@ -98,15 +107,19 @@ def fwd(q, k, v, rows=None):
     return o, rem
 
 
-def bwd(q, k, v, dout):
-    """Backward for upstream gradient dout = dL/do.  Returns (dq, dk, dv)."""
+def bwd(q, k, v, dout, r=None):
+    """Backward for upstream gradient dout = dL/do.  Returns (dq, dk, dv), and with
+    remainder-bias embeddings r also dr ([H,d], summed over the batch)."""
     shape = np.asarray(q).shape
     q4, k4, v4, g4 = _as4(q), _as4(k), _as4(v), _as4(dout)
     B, H, T, d = q4.shape
     dq = np.empty((B, H, T, d))
     dk = np.empty((B, H, T, d))
     dv = np.empty((B, H, T, d))
-    rc = _load().sb_oracle_bwd(_p(q4), _p(k4), _p(v4), _p(g4), _p(dq), _p(dk), _p(dv), B, H, T, d)
+    rr = _as_r(r, H, d)
+    dr = np.empty((H, d)) if rr is not None else None
+    rc = _load().sb_oracle_bwd(_p(q4), _p(k4), _p(v4), _p(rr), _p(g4), _p(dq), _p(dk), _p(dv), _p(dr), B, H, T, d)
     if rc != 0:
         raise RuntimeError(f"sb_oracle_bwd failed: {rc}")
-    return dq.reshape(shape), dk.reshape(shape), dv.reshape(shape)
+    out = (dq.reshape(shape), dk.reshape(shape), dv.reshape(shape))
+    return out + (dr.reshape(np.asarray(r).shape),) if rr is not None else out
