@@ -90,8 +90,9 @@ int sb_attn_fwd_f32(const float* q, const float* k, const float* v, float* o, fl
  * workspace: caller-owned device scratch of at least
  * sb_attn_bwd_workspace_bytes(B,H,T,d) bytes, 16-byte aligned; its contents on
  * entry do not matter and are garbage afterwards.  It holds two floats per
- * (query row, 32-key strip) and one int per 128-row block of queries and of keys:
- * B*H*(8*T*ceil(T/32) + 8*ceil(T/128)) bytes.  SB_ERR_WORKSPACE if it is NULL or
+ * (query row, 32-key strip), one int per 128-row block of queries and of keys and
+ * d floats per 128-row block (partial sums of sb_attn_bwd_rb's dr):
+ * B*H*(8*T*ceil(T/32) + (8 + 4*d)*ceil(T/128)) bytes.  SB_ERR_WORKSPACE if it is NULL or
  * too small.  sb_attn_bwd_workspace_bytes returns 0 for a bad shape.
  * No atomics are used: results are bit-reproducible from run to run.
  */
@@ -114,6 +115,24 @@ int sb_attn_bwd_dq(const void* q, const void* k, const void* v, const float* m, 
 int sb_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* dout,
                      float* dk, float* dv, void* workspace, size_t workspace_bytes,
                      int B, int H, int T, int d, void* stream);
+
+/*
+ * Remainder bias (Appendix C, the output equation with the remainder term): the part
+ * of the stick that no key took, 1 - sum_i A[i,j] = exp(m_j), goes to a learned
+ * embedding r of the head,  o_j = sum_{i<j} A[i,j] v_i + exp(m_j) r_h.
+ * r: bf16 [H, d] (one embedding per head, shared by the batch), device, 16-byte aligned.
+ *   sb_attn_fwd_rb  as sb_attn_fwd_train with the extra term; m may be NULL (inference).
+ *                   Row 0 has nothing to attend to: o_0 = r_h.
+ *   sb_attn_bwd_rb  as sb_attn_bwd for that forward (m from sb_attn_fwd_rb, same
+ *                   workspace rules); dZ gains -beta[i,j] exp(m_j) (dO_j . r_h), and
+ *                   dr [H, d] fp32 (fully overwritten) = sum over the batch and the rows
+ *                   of exp(m_j) dO_j, added in a fixed order (bit-reproducible).
+ */
+int sb_attn_fwd_rb(const void* q, const void* k, const void* v, const void* r, void* o, float* m,
+                   int B, int H, int T, int d, void* stream);
+int sb_attn_bwd_rb(const void* q, const void* k, const void* v, const void* r, const float* m,
+                   const void* dout, float* dq, float* dk, float* dv, float* dr,
+                   void* workspace, size_t workspace_bytes, int B, int H, int T, int d, void* stream);
 
 /*
  * Measurement aid (not part of the method): runs `iters` x 16 independent

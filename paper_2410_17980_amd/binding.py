@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libsbattn.so")
 EXPORTS = (
     "sb_attn_fwd", "sb_attn_fwd_halt", "sb_attn_fwd_train", "sb_attn_fwd_f32",
     "sb_attn_bwd_workspace_bytes", "sb_attn_bwd", "sb_attn_bwd_dq", "sb_attn_bwd_dkdv",
+    "sb_attn_fwd_rb", "sb_attn_bwd_rb",
     "sb_diag_mfma_rate",
     "sb_status_string", "sb_version",
 )
@@ -56,6 +57,10 @@ def load(build_if_missing: bool = True):
     lib.sb_attn_bwd_dq.restype = ci
     lib.sb_attn_bwd_dkdv.argtypes = [vp, vp, vp, vp, fp, fp, vp, ctypes.c_size_t, ci, ci, ci, ci, vp]
     lib.sb_attn_bwd_dkdv.restype = ci
+    lib.sb_attn_fwd_rb.argtypes = [vp, vp, vp, vp, vp, fp, ci, ci, ci, ci, vp]
+    lib.sb_attn_fwd_rb.restype = ci
+    lib.sb_attn_bwd_rb.argtypes = [vp, vp, vp, vp, fp, vp, fp, fp, fp, fp, vp, ctypes.c_size_t, ci, ci, ci, ci, vp]
+    lib.sb_attn_bwd_rb.restype = ci
     lib.sb_diag_mfma_rate.argtypes = [vp, ctypes.c_size_t, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.sb_diag_mfma_rate.restype = ci
     lib.sb_status_string.argtypes = [ci]
@@ -181,6 +186,41 @@ def sb_attn_bwd(q, k, v, m, dout, dq=None, dk=None, dv=None, workspace=None, str
                             B, H, T, d, _stream(stream))
     _check(rc, "sb_attn_bwd")
     return dq, dk, dv
+
+
+def sb_attn_fwd_rb(q, k, v, r, o=None, m=None, want_m=True, stream=None):
+    """bf16 forward with remainder bias r [H,d] (bf16).  Returns (o, m), or o when want_m is off."""
+    B, H, T, d = _dims(q)
+    if o is None:
+        o = torch.empty_like(q)
+    if m is None and want_m:
+        m = torch.empty((B, H, T), dtype=torch.float32, device=q.device)
+    rc = load().sb_attn_fwd_rb(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, q.shape, "k"),
+                               _ptr(v, torch.bfloat16, q.shape, "v"), _ptr(r, torch.bfloat16, (H, d), "r"),
+                               _ptr(o, torch.bfloat16, q.shape, "o"), _ptr(m, torch.float32, (B, H, T), "m"),
+                               B, H, T, d, _stream(stream))
+    _check(rc, "sb_attn_fwd_rb")
+    return (o, m) if m is not None else o
+
+
+def sb_attn_bwd_rb(q, k, v, r, m, dout, dq=None, dk=None, dv=None, dr=None, workspace=None, stream=None):
+    """bf16 backward with remainder bias.  Returns (dq, dk, dv, dr) in fp32; dr is [H,d]."""
+    B, H, T, d = _dims(q)
+    mk = lambda: torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    dq = mk() if dq is None else dq
+    dk = mk() if dk is None else dk
+    dv = mk() if dv is None else dv
+    dr = torch.empty((H, d), dtype=torch.float32, device=q.device) if dr is None else dr
+    workspace, ws_ptr, ws_bytes = _workspace(workspace, B, H, T, d, q.device)
+    rc = load().sb_attn_bwd_rb(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, q.shape, "k"),
+                               _ptr(v, torch.bfloat16, q.shape, "v"), _ptr(r, torch.bfloat16, (H, d), "r"),
+                               _ptr(m, torch.float32, (B, H, T), "m"),
+                               _ptr(dout, torch.bfloat16, q.shape, "dout"),
+                               _ptr(dq, torch.float32, q.shape, "dq"), _ptr(dk, torch.float32, q.shape, "dk"),
+                               _ptr(dv, torch.float32, q.shape, "dv"), _ptr(dr, torch.float32, (H, d), "dr"),
+                               ws_ptr, ws_bytes, B, H, T, d, _stream(stream))
+    _check(rc, "sb_attn_bwd_rb")
+    return dq, dk, dv, dr
 
 
 def _workspace(workspace, B, H, T, d, device):

@@ -233,13 +233,14 @@ __device__ __forceinline__ void stage_tile(const uint16_t* X, const uint16_t* Y,
 }
 
 // ------------------------------------------------------------------ dQ kernel
-template <int D, bool SLOW>
+template <int D, bool SLOW, bool RB>
 __global__ void __launch_bounds__(NTHREADS, SLOW ? 1 : 2)
 bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
-              const uint16_t* __restrict__ v, const float* __restrict__ m,
+              const uint16_t* __restrict__ v, const uint16_t* __restrict__ rb,
+              const float* __restrict__ m,
               const uint16_t* __restrict__ dout, float* __restrict__ dq,
               float* __restrict__ ca, float* __restrict__ cb, int* __restrict__ flags,
-              int T, int BH, int nqb, int nt32)
+              int T, int BH, int H, int nqb, int nt32)
 {
     using C = StageCfg<D>;
     __shared__ __attribute__((aligned(1024))) char smem[2 * C::STAGE];
@@ -384,11 +385,28 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         }
         a2 = -m[bh * (long)T + jq] * SB_LOG2E;
         bsum = 0.0f;
+        if constexpr (RB) {
+            // remainder bias (Appendix C): the unused stick exp(m) acts like one more weight
+            // in front of key 0, with "value" r_head: the cumulative sum of G starts at
+            // exp(m_j) (dO_j . r_head)
+            const u32x4* rs = reinterpret_cast<const u32x4*>(rb + (bh % H) * D + 8 * hh);
+            float dot = 0.0f;
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+                const bf16x8 rr = __builtin_bit_cast(bf16x8, rs[2 * s]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot += (float)gf[s][e] * (float)rr[e];
+            }
+            float d_lo, d_hi;
+            both_halves(dot, d_lo, d_hi);
+            bsum = fast_exp2(-a2) * (d_lo + d_hi);
+        }
         // wait for these loads (and the first block's stores) once, before the staging
         // loads, which are counted in the same counter behind the compiler's back
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) { asm volatile("" :: "v"(qf[s])); asm volatile("" :: "v"(gf[s])); }
         asm volatile("" :: "v"(a2));
+        asm volatile("" :: "v"(bsum));
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
         for (int b = 0; b < D / 32; ++b)
@@ -700,13 +718,66 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     }
 }
 
-// workspace layout: ca[BH][nt32][T], cb[BH][nt32][T] (fp32), then the per-block flags of
-// the two kernels (int): [BH][nqb], [BH][nkb]
+// ------------------------------------------------------------------ gradient of the remainder bias
+// dr[h][c] = sum over the batch and the rows j of exp(m_j) dO[j][c] (Appendix C: the
+// output holds (stick left of row j) * r_h).  Two deterministic steps: per (batch entry,
+// head, 128-row chunk) partial sums, then one thread per (h, c) adds them in a fixed order.
+constexpr int DR_ROWS = 128;
+
 template <int D>
-hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, const float* m,
-                      const uint16_t* dout, float* dq, float* dk, float* dv, float* workspace,
-                      int BH, int T, int passes, hipStream_t stream)
+__global__ void __launch_bounds__(NTHREADS)
+bwd_drb_partial_kernel(const float* __restrict__ m, const uint16_t* __restrict__ dout,
+                       float* __restrict__ part, int T, int nchunk)
 {
+    constexpr int CP = D / 2;                 // column pairs
+    constexpr int RG = NTHREADS / CP;         // row groups
+    __shared__ float red[RG][D];
+    const long bh = blockIdx.y;
+    const int chunk = blockIdx.x;
+    const int cp = threadIdx.x % CP, rg = threadIdx.x / CP;
+    const int j1 = min(T, (chunk + 1) * DR_ROWS);
+    float a0 = 0.0f, a1 = 0.0f;
+    for (int j = chunk * DR_ROWS + rg; j < j1; j += RG) {
+        const float w = __expf(m[bh * (long)T + j]);
+        const uint32_t g = *reinterpret_cast<const uint32_t*>(dout + (bh * (long)T + j) * D + 2 * cp);
+        a0 += w * __builtin_bit_cast(float, g << 16);
+        a1 += w * __builtin_bit_cast(float, g & 0xffff0000u);
+    }
+    red[rg][2 * cp] = a0;
+    red[rg][2 * cp + 1] = a1;
+    __syncthreads();
+    if (threadIdx.x < D) {
+        float s = 0.0f;
+#pragma unroll
+        for (int g = 0; g < RG; ++g) s += red[g][threadIdx.x];
+        part[(bh * nchunk + chunk) * D + threadIdx.x] = s;
+    }
+}
+
+template <int D>
+__global__ void __launch_bounds__(D)
+bwd_drb_sum_kernel(const float* __restrict__ part, float* __restrict__ drb, int B, int H, int nchunk)
+{
+    const int h = blockIdx.x, c = threadIdx.x;
+    float s = 0.0f;
+    for (int b = 0; b < B; ++b) {
+        const float* p = part + ((long)(b * (long)H + h) * nchunk) * D + c;
+        float sb = 0.0f;
+        for (int ch = 0; ch < nchunk; ++ch) sb += p[(long)ch * D];
+        s += sb;
+    }
+    drb[h * D + c] = s;
+}
+
+// workspace layout: ca[BH][nt32][T], cb[BH][nt32][T] (fp32), then the per-block flags of
+// the two kernels (int): [BH][nqb], [BH][nkb], then the partial sums of the remainder-bias
+// gradient (fp32): [BH][nchunk][D]
+template <int D>
+hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
+                      const float* m, const uint16_t* dout, float* dq, float* dk, float* dv,
+                      float* drb, float* workspace, int B, int H, int T, int passes, hipStream_t stream)
+{
+    const int BH = B * H;
     const int nt32 = (T + 31) / 32;
     const int nqb = (T + BQ - 1) / BQ;
     const int nkb = (T + BKW - 1) / BKW;
@@ -714,17 +785,36 @@ hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, c
     float* cb = ca + (long)BH * nt32 * T;
     int* fq = reinterpret_cast<int*>(cb + (long)BH * nt32 * T);
     int* fk = fq + (long)BH * nqb;
+    float* part = reinterpret_cast<float*>(fk + (long)BH * nkb);
+    const int nchunk = (T + DR_ROWS - 1) / DR_ROWS;
     const long bq = 8L * ((BH + 7) / 8) * ((nqb + 1) / 2);
     const long bk = 8L * ((BH + 7) / 8) * ((nkb + 1) / 2);
     if (bq > 0x7fffffffL || bk > 0x7fffffffL) return hipErrorInvalidValue;
     hipError_t e = hipSuccess;
     if (passes & 1) {
-        hipLaunchKernelGGL((bwd_dq_kernel<D, false>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
-                           q, k, v, m, dout, dq, ca, cb, fq, T, BH, nqb, nt32);
+        if (rb) {
+            hipLaunchKernelGGL((bwd_dq_kernel<D, false, true>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
+                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, nqb, nt32);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            hipLaunchKernelGGL((bwd_dq_kernel<D, true, true>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
+                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, nqb, nt32);
+        } else {
+            hipLaunchKernelGGL((bwd_dq_kernel<D, false, false>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
+                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, nqb, nt32);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            hipLaunchKernelGGL((bwd_dq_kernel<D, true, false>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
+                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, nqb, nt32);
+        }
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL((bwd_dq_kernel<D, true>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
-                           q, k, v, m, dout, dq, ca, cb, fq, T, BH, nqb, nt32);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if (drb) {
+            if (BH > 65535) return hipErrorInvalidValue;
+            hipLaunchKernelGGL((bwd_drb_partial_kernel<D>), dim3((unsigned)nchunk, (unsigned)BH), dim3(NTHREADS), 0,
+                               stream, m, dout, part, T, nchunk);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            hipLaunchKernelGGL((bwd_drb_sum_kernel<D>), dim3((unsigned)H), dim3(D), 0, stream,
+                               part, drb, B, H, nchunk);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
     }
     if (passes & 2) {
         hipLaunchKernelGGL((bwd_dkv_kernel<D, false>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
@@ -739,20 +829,21 @@ hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, c
 
 }  // namespace
 
-size_t bwd_workspace_bytes(int B, int H, int T)
+size_t bwd_workspace_bytes(int B, int H, int T, int d)
 {
     const size_t nt32 = (size_t)(T + 31) / 32;
     const size_t nblk = (size_t)(T + BQ - 1) / BQ + (size_t)(T + BKW - 1) / BKW;
-    return (2 * sizeof(float) * nt32 * T + sizeof(int) * nblk) * (size_t)B * H;
+    const size_t nchunk = (size_t)(T + DR_ROWS - 1) / DR_ROWS;
+    return (2 * sizeof(float) * nt32 * T + sizeof(int) * nblk + sizeof(float) * nchunk * d) * (size_t)B * H;
 }
 
-hipError_t launch_bwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const float* m,
-                           const uint16_t* dout, float* dq, float* dk, float* dv, float* workspace,
+hipError_t launch_bwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
+                           const float* m, const uint16_t* dout, float* dq, float* dk, float* dv,
+                           float* drb, float* workspace,
                            int B, int H, int T, int d, int passes, hipStream_t stream)
 {
-    const int BH = B * H;
-    if (d == 64) return launch_one<64>(q, k, v, m, dout, dq, dk, dv, workspace, BH, T, passes, stream);
-    return launch_one<128>(q, k, v, m, dout, dq, dk, dv, workspace, BH, T, passes, stream);
+    if (d == 64) return launch_one<64>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, B, H, T, passes, stream);
+    return launch_one<128>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, B, H, T, passes, stream);
 }
 
 }  // namespace sb

@@ -63,11 +63,12 @@ template <int D> struct FwdCfg {
 
 template <bool B> using bc = std::integral_constant<bool, B>;
 
-template <int D, bool WRITE_M, bool HALT>
+template <int D, bool WRITE_M, bool HALT, bool RB>
 __global__ void __launch_bounds__(64 * NW, 2)
 fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
-                const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ m,
-                int T, int BH, int nqb, float halt_carry, unsigned long long* __restrict__ tile_counts)
+                const uint16_t* __restrict__ v, const uint16_t* __restrict__ rb,
+                uint16_t* __restrict__ o, float* __restrict__ m,
+                int T, int BH, int H, int nqb, float halt_carry, unsigned long long* __restrict__ tile_counts)
 {
     using C = FwdCfg<D>;
     constexpr int NPW = C::NPW;
@@ -356,6 +357,22 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 
         // ---- store.  oacc[b][r] is query row 8*(r/4) + 4*hh + r%4, column 32b + n.
         if (wave_live) {
+            if constexpr (RB) {
+                // remainder bias (Appendix C): o_j += (stick left of row j) * r_head.  The
+                // lanes n of both half-waves hold the carry of row q0 + n.
+                const float rem = fast_exp2(-a);
+                const uint16_t* rh = rb + (bh % H) * D;
+                float rc[D / 32];
+#pragma unroll
+                for (int b = 0; b < D / 32; ++b)
+                    rc[b] = __builtin_bit_cast(float, (uint32_t)rh[32 * b + n] << 16);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float rr = __shfl(rem, 8 * (r >> 2) + 4 * hh + (r & 3));
+#pragma unroll
+                    for (int b = 0; b < D / 32; ++b) oacc[b][r] += rr * rc[b];
+                }
+            }
             uint16_t* Og = o + bh * (long)T * D;
             const bool full = q0 + 32 <= T;
 #pragma unroll
@@ -374,29 +391,33 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     }
 }
 
-template <int D, bool WRITE_M, bool HALT>
-hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o, float* m,
-                      int BH, int T, float halt_carry, unsigned long long* tile_counts, hipStream_t stream)
+template <int D, bool WRITE_M, bool HALT, bool RB>
+hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
+                      uint16_t* o, float* m, int BH, int H, int T, float halt_carry,
+                      unsigned long long* tile_counts, hipStream_t stream)
 {
     const int nqb = (T + BQ - 1) / BQ;
     const long blocks = 8L * ((BH + 7) / 8) * ((nqb + 1) / 2);
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((fwd_bf16_kernel<D, WRITE_M, HALT>), dim3((unsigned)blocks), dim3(64 * NW), 0, stream,
-                       q, k, v, o, m, T, BH, nqb, halt_carry, tile_counts);
+    hipLaunchKernelGGL((fwd_bf16_kernel<D, WRITE_M, HALT, RB>), dim3((unsigned)blocks), dim3(64 * NW), 0, stream,
+                       q, k, v, rb, o, m, T, BH, H, nqb, halt_carry, tile_counts);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o,
-                           float* m, int B, int H, int T, int d, hipStream_t stream)
+hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
+                           uint16_t* o, float* m, int B, int H, int T, int d, hipStream_t stream)
 {
     const int BH = B * H;
-    if (d == 64)
-        return m ? launch_one<64, true, false>(q, k, v, o, m, BH, T, 0.0f, nullptr, stream)
-                 : launch_one<64, false, false>(q, k, v, o, m, BH, T, 0.0f, nullptr, stream);
-    return m ? launch_one<128, true, false>(q, k, v, o, m, BH, T, 0.0f, nullptr, stream)
-             : launch_one<128, false, false>(q, k, v, o, m, BH, T, 0.0f, nullptr, stream);
+#define SB_FWD(DD, WM, RBV) launch_one<DD, WM, false, RBV>(q, k, v, rb, o, m, BH, H, T, 0.0f, nullptr, stream)
+    if (d == 64) {
+        if (rb) return m ? SB_FWD(64, true, true) : SB_FWD(64, false, true);
+        return m ? SB_FWD(64, true, false) : SB_FWD(64, false, false);
+    }
+    if (rb) return m ? SB_FWD(128, true, true) : SB_FWD(128, false, true);
+    return m ? SB_FWD(128, true, false) : SB_FWD(128, false, false);
+#undef SB_FWD
 }
 
 hipError_t launch_fwd_bf16_halt(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o,
@@ -405,8 +426,9 @@ hipError_t launch_fwd_bf16_halt(const uint16_t* q, const uint16_t* k, const uint
 {
     const int BH = B * H;
     const float halt_carry = -log2f(eps);               // carry = -log2(stick left)
-    if (d == 64) return launch_one<64, false, true>(q, k, v, o, nullptr, BH, T, halt_carry, tile_counts, stream);
-    return launch_one<128, false, true>(q, k, v, o, nullptr, BH, T, halt_carry, tile_counts, stream);
+    if (d == 64)
+        return launch_one<64, false, true, false>(q, k, v, nullptr, o, nullptr, BH, H, T, halt_carry, tile_counts, stream);
+    return launch_one<128, false, true, false>(q, k, v, nullptr, o, nullptr, BH, H, T, halt_carry, tile_counts, stream);
 }
 
 }  // namespace sb

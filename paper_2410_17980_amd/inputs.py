@@ -115,6 +115,13 @@ def biased_gaussian(B: int, H: int, T: int, d: int, seed: int, shift: float,
     return tuple(_round(t, dtype) for t in out)
 
 
+def remainder_embedding(H: int, d: int, seed: int, dtype: str = "bf16"):
+    """One N(0,1) embedding per head for the remainder bias, r [H, d]."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    return _round(torch.randn(H, d, generator=g, dtype=torch.float32), dtype)
+
+
 def scaled_gaussian(B: int, H: int, T: int, d: int, seed: int, gain: float,
                     dtype: str = "bf16", with_dout: bool = False):
     """N(0,1) tensors with k multiplied by gain (very sharp sigma for large gain)."""

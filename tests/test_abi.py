@@ -60,10 +60,17 @@ def test_argument_validation_without_a_gpu(lib):
     assert lib.sb_attn_fwd_f32(p, p, p, p, odd, 1, 1, 8, 64, None) == -4
     assert lib.sb_attn_bwd(p, p, p, None, p, p, p, p, None, 0, 1, 1, 8, 64, None) == -1
     assert lib.sb_attn_bwd(p, p, p, p, p, p, p, p, None, 0, 1, 1, 8, 32, None) == -3
+    # remainder bias: r and dr are required
+    assert lib.sb_attn_fwd_rb(p, p, p, None, p, None, 1, 1, 8, 64, None) == -1
+    assert lib.sb_attn_fwd_rb(p, p, p, odd, p, None, 1, 1, 8, 64, None) == -4
+    assert lib.sb_attn_bwd_rb(p, p, p, None, p, p, p, p, p, p, p, 1 << 20, 1, 1, 8, 64, None) == -1
+    assert lib.sb_attn_bwd_rb(p, p, p, p, p, p, p, p, p, None, p, 1 << 20, 1, 1, 8, 64, None) == -1
+    assert lib.sb_attn_bwd_rb(p, p, p, p, p, p, p, p, p, p, None, 0, 1, 1, 8, 64, None) == -6
     # workspace: size query, then missing / too small / misaligned workspace
     need = lib.sb_attn_bwd_workspace_bytes(2, 3, 100, 64)
-    # two floats per (row, 32-key strip) and one int per 128-row query block and key block
-    assert need == 2 * 3 * (8 * 100 * 4 + 4 * (1 + 1))
+    # two floats per (row, 32-key strip), one int per 128-row query block and key block,
+    # d floats per 128-row block
+    assert need == 2 * 3 * (8 * 100 * 4 + 4 * (1 + 1) + 4 * 64 * 1)
     assert lib.sb_attn_bwd_workspace_bytes(2, 3, 100, 65) == 0
     assert lib.sb_attn_bwd(p, p, p, p, p, p, p, p, None, 0, 2, 3, 100, 64, None) == -6
     assert lib.sb_attn_bwd(p, p, p, p, p, p, p, p, p, need - 1, 2, 3, 100, 64, None) == -6
