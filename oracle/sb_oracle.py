@@ -123,3 +123,32 @@ def bwd(q, k, v, dout, r=None):
         raise RuntimeError(f"sb_oracle_bwd failed: {rc}")
     out = (dq.reshape(shape), dk.reshape(shape), dv.reshape(shape))
     return out + (dr.reshape(np.asarray(r).shape),) if rr is not None else out
+
+
+def _expand_kv(x, H):
+    """[B,Hkv,T,d] -> [B,H,T,d]: query head h reads kv head h // (H // Hkv)."""
+    x = np.asarray(x, dtype=np.float64)
+    Hkv = x.shape[1]
+    assert H % Hkv == 0, "query heads must be a multiple of kv heads"
+    return np.repeat(x, H // Hkv, axis=1)
+
+
+def fwd_gqa(q, k, v, rows=None, r=None):
+    """Grouped kv heads (the paper's larger models pair 12 query heads with 4 kv heads,
+    Appendix C model table): q [B,H,T,d], k,v [B,Hkv,T,d]; consecutive groups of H/Hkv
+    query heads attend to the same keys and values.  Plain definition: copy each kv
+    head to its group and run Eq. 1."""
+    H = np.asarray(q).shape[1]
+    return fwd(q, _expand_kv(k, H), _expand_kv(v, H), rows=rows, r=r)
+
+
+def bwd_gqa(q, k, v, dout, r=None):
+    """Gradients for grouped kv heads: dq per query head; dk, dv [B,Hkv,T,d] are the sums
+    over the group of the per-head gradients (a shared tensor collects every use)."""
+    q = np.asarray(q, dtype=np.float64)
+    B, H, T, d = q.shape
+    Hkv = np.asarray(k).shape[1]
+    out = bwd(q, _expand_kv(k, H), _expand_kv(v, H), dout, r=r)
+    dk = out[1].reshape(B, Hkv, H // Hkv, T, d).sum(axis=2)
+    dv = out[2].reshape(B, Hkv, H // Hkv, T, d).sum(axis=2)
+    return (out[0], dk, dv) + tuple(out[3:])
