@@ -135,6 +135,23 @@ int sb_attn_bwd_rb(const void* q, const void* k, const void* v, const void* r, c
                    void* workspace, size_t workspace_bytes, int B, int H, int T, int d, void* stream);
 
 /*
+ * Grouped kv heads (the paper's larger models pair 12 query heads with 4 kv heads;
+ * Appendix C, model table): q, o, dout, dq are [B, H, T, d], k, v, dk, dv are
+ * [B, Hkv, T, d], H a multiple of Hkv (SB_ERR_SHAPE otherwise); query head h attends to
+ * kv head h / (H / Hkv).  These are the general forms of the calls above:
+ *   sb_attn_fwd_gqa  forward; r (remainder bias, [H, d] bf16) and m may each be NULL.
+ *   sb_attn_bwd_gqa  backward; r and dr both NULL or both given; dk, dv are summed over
+ *                    the query heads of each group inside one workgroup's registers (no
+ *                    atomics, bit-reproducible).  Workspace as for sb_attn_bwd with the
+ *                    number of query heads: sb_attn_bwd_workspace_bytes(B, H, T, d).
+ */
+int sb_attn_fwd_gqa(const void* q, const void* k, const void* v, const void* r, void* o, float* m,
+                    int B, int H, int Hkv, int T, int d, void* stream);
+int sb_attn_bwd_gqa(const void* q, const void* k, const void* v, const void* r, const float* m,
+                    const void* dout, float* dq, float* dk, float* dv, float* dr,
+                    void* workspace, size_t workspace_bytes, int B, int H, int Hkv, int T, int d, void* stream);
+
+/*
  * Measurement aid (not part of the method): runs `iters` x 16 independent
  * 32x32x16 bf16 MFMAs per wavefront, two wavefronts per SIMD on the whole chip,
  * on operands taken from `operands` (device, bf16, at least 1 MiB, 16-byte

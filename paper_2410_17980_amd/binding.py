@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libsbattn.so")
 EXPORTS = (
     "sb_attn_fwd", "sb_attn_fwd_halt", "sb_attn_fwd_train", "sb_attn_fwd_f32",
     "sb_attn_bwd_workspace_bytes", "sb_attn_bwd", "sb_attn_bwd_dq", "sb_attn_bwd_dkdv",
-    "sb_attn_fwd_rb", "sb_attn_bwd_rb",
+    "sb_attn_fwd_rb", "sb_attn_bwd_rb", "sb_attn_fwd_gqa", "sb_attn_bwd_gqa",
     "sb_diag_mfma_rate",
     "sb_status_string", "sb_version",
 )
@@ -61,6 +61,11 @@ def load(build_if_missing: bool = True):
     lib.sb_attn_fwd_rb.restype = ci
     lib.sb_attn_bwd_rb.argtypes = [vp, vp, vp, vp, fp, vp, fp, fp, fp, fp, vp, ctypes.c_size_t, ci, ci, ci, ci, vp]
     lib.sb_attn_bwd_rb.restype = ci
+    lib.sb_attn_fwd_gqa.argtypes = [vp, vp, vp, vp, vp, fp, ci, ci, ci, ci, ci, vp]
+    lib.sb_attn_fwd_gqa.restype = ci
+    lib.sb_attn_bwd_gqa.argtypes = [vp, vp, vp, vp, fp, vp, fp, fp, fp, fp, vp, ctypes.c_size_t,
+                                    ci, ci, ci, ci, ci, vp]
+    lib.sb_attn_bwd_gqa.restype = ci
     lib.sb_diag_mfma_rate.argtypes = [vp, ctypes.c_size_t, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.sb_diag_mfma_rate.restype = ci
     lib.sb_status_string.argtypes = [ci]
@@ -221,6 +226,48 @@ def sb_attn_bwd_rb(q, k, v, r, m, dout, dq=None, dk=None, dv=None, dr=None, work
                                ws_ptr, ws_bytes, B, H, T, d, _stream(stream))
     _check(rc, "sb_attn_bwd_rb")
     return dq, dk, dv, dr
+
+
+def sb_attn_fwd_gqa(q, k, v, r=None, o=None, m=None, want_m=True, stream=None):
+    """bf16 forward with grouped kv heads: q [B,H,T,d], k, v [B,Hkv,T,d]; optional remainder
+    bias r [H,d].  Returns (o, m), or o when want_m is off."""
+    B, H, T, d = _dims(q)
+    Hkv = _dims(k)[1]
+    if o is None:
+        o = torch.empty_like(q)
+    if m is None and want_m:
+        m = torch.empty((B, H, T), dtype=torch.float32, device=q.device)
+    kv_shape = (B, Hkv, T, d)
+    rc = load().sb_attn_fwd_gqa(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, kv_shape, "k"),
+                                _ptr(v, torch.bfloat16, kv_shape, "v"), _ptr(r, torch.bfloat16, (H, d), "r"),
+                                _ptr(o, torch.bfloat16, q.shape, "o"), _ptr(m, torch.float32, (B, H, T), "m"),
+                                B, H, Hkv, T, d, _stream(stream))
+    _check(rc, "sb_attn_fwd_gqa")
+    return (o, m) if m is not None else o
+
+
+def sb_attn_bwd_gqa(q, k, v, m, dout, r=None, dq=None, dk=None, dv=None, dr=None, workspace=None, stream=None):
+    """bf16 backward with grouped kv heads.  Returns (dq, dk, dv) in fp32 (dk, dv [B,Hkv,T,d]),
+    and dr [H,d] as a fourth item when r is given."""
+    B, H, T, d = _dims(q)
+    Hkv = _dims(k)[1]
+    kv_shape = (B, Hkv, T, d)
+    mk = lambda shape: torch.empty(shape, dtype=torch.float32, device=q.device)
+    dq = mk(q.shape) if dq is None else dq
+    dk = mk(kv_shape) if dk is None else dk
+    dv = mk(kv_shape) if dv is None else dv
+    if r is not None and dr is None:
+        dr = mk((H, d))
+    workspace, ws_ptr, ws_bytes = _workspace(workspace, B, H, T, d, q.device)
+    rc = load().sb_attn_bwd_gqa(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, kv_shape, "k"),
+                                _ptr(v, torch.bfloat16, kv_shape, "v"), _ptr(r, torch.bfloat16, (H, d), "r"),
+                                _ptr(m, torch.float32, (B, H, T), "m"),
+                                _ptr(dout, torch.bfloat16, q.shape, "dout"),
+                                _ptr(dq, torch.float32, q.shape, "dq"), _ptr(dk, torch.float32, kv_shape, "dk"),
+                                _ptr(dv, torch.float32, kv_shape, "dv"), _ptr(dr, torch.float32, (H, d), "dr"),
+                                ws_ptr, ws_bytes, B, H, Hkv, T, d, _stream(stream))
+    _check(rc, "sb_attn_bwd_gqa")
+    return (dq, dk, dv, dr) if r is not None else (dq, dk, dv)
 
 
 def _workspace(workspace, B, H, T, d, device):

@@ -31,22 +31,30 @@ int sb_attn_fwd(const void* q, const void* k, const void* v, void* o,
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return SB_ERR_ALIGN;
     hipError_t e = sb::launch_fwd_bf16(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                                        static_cast<const uint16_t*>(v), nullptr, static_cast<uint16_t*>(o),
-                                       nullptr, B, H, T, d, static_cast<hipStream_t>(stream));
+                                       nullptr, B, H, H, T, d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
+int sb_attn_fwd_gqa(const void* q, const void* k, const void* v, const void* r, void* o, float* m,
+                    int B, int H, int Hkv, int T, int d, void* stream)
+{
+    if (!q || !k || !v || !o) return SB_ERR_NULL;
+    if (int rc = check_shape(B, H, T, d)) return rc;
+    if (Hkv < 1 || H % Hkv != 0) return SB_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(r) || !aligned16(o) || !aligned16(m))
+        return SB_ERR_ALIGN;
+    hipError_t e = sb::launch_fwd_bf16(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                                       static_cast<const uint16_t*>(v), static_cast<const uint16_t*>(r),
+                                       static_cast<uint16_t*>(o), m, B, H, Hkv, T, d,
+                                       static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
 }
 
 int sb_attn_fwd_rb(const void* q, const void* k, const void* v, const void* r, void* o, float* m,
                    int B, int H, int T, int d, void* stream)
 {
-    if (!q || !k || !v || !r || !o) return SB_ERR_NULL;
-    if (int rc = check_shape(B, H, T, d)) return rc;
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(r) || !aligned16(o) || !aligned16(m))
-        return SB_ERR_ALIGN;
-    hipError_t e = sb::launch_fwd_bf16(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
-                                       static_cast<const uint16_t*>(v), static_cast<const uint16_t*>(r),
-                                       static_cast<uint16_t*>(o), m, B, H, T, d,
-                                       static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+    if (!r) return SB_ERR_NULL;
+    return sb_attn_fwd_gqa(q, k, v, r, o, m, B, H, H, T, d, stream);
 }
 
 int sb_attn_fwd_halt(const void* q, const void* k, const void* v, void* o,
@@ -73,7 +81,7 @@ int sb_attn_fwd_train(const void* q, const void* k, const void* v, void* o, floa
         return SB_ERR_ALIGN;
     hipError_t e = sb::launch_fwd_bf16(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
                                        static_cast<const uint16_t*>(v), nullptr, static_cast<uint16_t*>(o),
-                                       m, B, H, T, d, static_cast<hipStream_t>(stream));
+                                       m, B, H, H, T, d, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
 }
 
@@ -100,13 +108,14 @@ namespace {
 
 int bwd_checked(const void* q, const void* k, const void* v, const void* r, const float* m, const void* dout,
                 float* dq, float* dk, float* dv, float* dr, void* workspace, size_t workspace_bytes,
-                int B, int H, int T, int d, int passes, void* stream)
+                int B, int H, int Hkv, int T, int d, int passes, void* stream)
 {
     if (!q || !k || !v || !dout) return SB_ERR_NULL;
     if ((r == nullptr) != (dr == nullptr)) return SB_ERR_NULL;
     if ((passes & 1) && (!m || !dq)) return SB_ERR_NULL;
     if ((passes & 2) && (!dk || !dv)) return SB_ERR_NULL;
     if (int rc = check_shape(B, H, T, d)) return rc;
+    if (Hkv < 1 || H % Hkv != 0) return SB_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(m) || !aligned16(dout) ||
         !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(workspace) ||
         !aligned16(r) || !aligned16(dr))
@@ -116,7 +125,7 @@ int bwd_checked(const void* q, const void* k, const void* v, const void* r, cons
                                        static_cast<const uint16_t*>(v), static_cast<const uint16_t*>(r), m,
                                        static_cast<const uint16_t*>(dout), dq, dk, dv, dr,
                                        static_cast<float*>(workspace),
-                                       B, H, T, d, passes, static_cast<hipStream_t>(stream));
+                                       B, H, Hkv, T, d, passes, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
 }
 
@@ -129,7 +138,7 @@ int sb_attn_bwd(const void* q, const void* k, const void* v, const float* m, con
                 int B, int H, int T, int d, void* stream)
 {
     return bwd_checked(q, k, v, nullptr, m, dout, dq, dk, dv, nullptr, workspace, workspace_bytes,
-                       B, H, T, d, 3, stream);
+                       B, H, H, T, d, 3, stream);
 }
 
 int sb_attn_bwd_rb(const void* q, const void* k, const void* v, const void* r, const float* m,
@@ -137,7 +146,14 @@ int sb_attn_bwd_rb(const void* q, const void* k, const void* v, const void* r, c
                    void* workspace, size_t workspace_bytes, int B, int H, int T, int d, void* stream)
 {
     if (!r || !dr) return SB_ERR_NULL;
-    return bwd_checked(q, k, v, r, m, dout, dq, dk, dv, dr, workspace, workspace_bytes, B, H, T, d, 3, stream);
+    return bwd_checked(q, k, v, r, m, dout, dq, dk, dv, dr, workspace, workspace_bytes, B, H, H, T, d, 3, stream);
+}
+
+int sb_attn_bwd_gqa(const void* q, const void* k, const void* v, const void* r, const float* m,
+                    const void* dout, float* dq, float* dk, float* dv, float* dr,
+                    void* workspace, size_t workspace_bytes, int B, int H, int Hkv, int T, int d, void* stream)
+{
+    return bwd_checked(q, k, v, r, m, dout, dq, dk, dv, dr, workspace, workspace_bytes, B, H, Hkv, T, d, 3, stream);
 }
 
 int sb_attn_bwd_dq(const void* q, const void* k, const void* v, const float* m, const void* dout,
@@ -145,7 +161,7 @@ int sb_attn_bwd_dq(const void* q, const void* k, const void* v, const float* m, 
                    int B, int H, int T, int d, void* stream)
 {
     return bwd_checked(q, k, v, nullptr, m, dout, dq, nullptr, nullptr, nullptr, workspace, workspace_bytes,
-                       B, H, T, d, 1, stream);
+                       B, H, H, T, d, 1, stream);
 }
 
 int sb_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* dout,
@@ -153,7 +169,7 @@ int sb_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* do
                      int B, int H, int T, int d, void* stream)
 {
     return bwd_checked(q, k, v, nullptr, nullptr, dout, nullptr, dk, dv, nullptr, workspace, workspace_bytes,
-                       B, H, T, d, 2, stream);
+                       B, H, H, T, d, 2, stream);
 }
 
 int sb_diag_mfma_rate(const void* operands, size_t operand_bytes, int iters, unsigned long long* ticks,

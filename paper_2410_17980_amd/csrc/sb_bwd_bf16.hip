@@ -240,7 +240,7 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
               const float* __restrict__ m,
               const uint16_t* __restrict__ dout, float* __restrict__ dq,
               float* __restrict__ ca, float* __restrict__ cb, int* __restrict__ flags,
-              int T, int BH, int H, int nqb, int nt32)
+              int T, int BH, int H, int G, int nqb, int nt32)
 {
     using C = StageCfg<D>;
     __shared__ __attribute__((aligned(1024))) char smem[2 * C::STAGE];
@@ -260,8 +260,10 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int gg = lane >> 4, li = lane & 15;
 
     const long base = bh * (long)T * D;
-    const uint16_t* Kg = k + base;
-    const uint16_t* Vg = v + base;
+    // grouped kv heads: G consecutive query heads read the same K and V
+    const long kvbase = (G == 1 ? bh : (bh / H) * (H / G) + (bh % H) / G) * (long)T * D;
+    const uint16_t* Kg = k + kvbase;
+    const uint16_t* Vg = v + kvbase;
 
     // per-lane LDS offsets inside a 32-row subtile
     int aoff[D / 16];                       // A-operand reads (K rows for S^T, V rows for P^T)
@@ -471,16 +473,17 @@ template <int D> struct DkvCfg {
     static constexpr int LDS_BYTES = T_OFF + NW * T_WAVE;
 };
 
-template <int D, bool SLOW>
+template <int D, bool SLOW, bool GQA>
 __global__ void __launch_bounds__(NTHREADS, 1)
 bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                const uint16_t* __restrict__ v, const uint16_t* __restrict__ dout,
                const float* __restrict__ ca, const float* __restrict__ cb,
                float* __restrict__ dk, float* __restrict__ dv, int* __restrict__ flags,
-               int T, int BH, int nkb, int nt32)
+               int T, int BH, int H, int G_arg, int nkb, int nt32)
 {
     using C = StageCfg<D>;
     using CK = DkvCfg<D>;
+    const int G = GQA ? G_arg : 1;                      // query heads per kv head
     __shared__ __attribute__((aligned(1024))) char smem[CK::LDS_BYTES];
     __shared__ int s_dirty;
 
@@ -497,9 +500,12 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int n = lane & 31, hh = lane >> 5;
     const int gg = lane >> 4, li = lane & 15;
 
+    // bh counts kv heads here (BH = B * H / G of them); its G query heads are qh0 .. qh0+G-1
     const long base = bh * (long)T * D;
-    const uint16_t* Qg = q + base;
-    const uint16_t* Gg = dout + base;
+    const int Hkv = H / G;
+    const long qh0 = G == 1 ? bh : (bh / Hkv) * H + (bh % Hkv) * G;
+    const uint16_t* Qg = nullptr;
+    const uint16_t* Gg = nullptr;
 
     // per-lane LDS offsets inside a 32-row Q / dO subtile (natural row order)
     int boff[D / 16];                       // B-operand reads: row = query n
@@ -637,8 +643,14 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         for (int b = 0; b < D / 32; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) { dkacc[b][r] = 0.0f; dvacc[b][r] = 0.0f; }
-        cag = ca + (bh * (long)nt32 + kt32) * T;
-        cbg = cb + (bh * (long)nt32 + kt32) * T;
+        // the query heads of the group one after the other, into the same accumulators
+        for (int g = 0; g < G; ++g) {
+        const long qbh = qh0 + g;
+        Qg = q + qbh * (long)T * D;
+        Gg = dout + qbh * (long)T * D;
+        cag = ca + (qbh * (long)nt32 + kt32) * T;
+        cbg = cb + (qbh * (long)nt32 + kt32) * T;
+        if (g > 0) barrier_nofence();                        // everyone is done with the stages of the head before
 
         // ---- sweep over 64-row query tiles, from the block's diagonal to the end;
         // iteration it handles tile jt0 + it in buffer it & 1.  The carries of a tile are
@@ -693,6 +705,7 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             }
         }
         dma_wait<0>();
+        }
 
         // ---- store: acc[b][r] is key row k0 + 8*(r/4) + 4*hh + r%4, column 32b + n
         if (wave_live) {
@@ -775,9 +788,11 @@ bwd_drb_sum_kernel(const float* __restrict__ part, float* __restrict__ drb, int 
 template <int D>
 hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
                       const float* m, const uint16_t* dout, float* dq, float* dk, float* dv,
-                      float* drb, float* workspace, int B, int H, int T, int passes, hipStream_t stream)
+                      float* drb, float* workspace, int B, int H, int Hkv, int T, int passes, hipStream_t stream)
 {
     const int BH = B * H;
+    const int BHkv = B * Hkv;
+    const int G = H / Hkv;
     const int nt32 = (T + 31) / 32;
     const int nqb = (T + BQ - 1) / BQ;
     const int nkb = (T + BKW - 1) / BKW;
@@ -788,22 +803,22 @@ hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, c
     float* part = reinterpret_cast<float*>(fk + (long)BH * nkb);
     const int nchunk = (T + DR_ROWS - 1) / DR_ROWS;
     const long bq = 8L * ((BH + 7) / 8) * ((nqb + 1) / 2);
-    const long bk = 8L * ((BH + 7) / 8) * ((nkb + 1) / 2);
+    const long bk = 8L * ((BHkv + 7) / 8) * ((nkb + 1) / 2);
     if (bq > 0x7fffffffL || bk > 0x7fffffffL) return hipErrorInvalidValue;
     hipError_t e = hipSuccess;
     if (passes & 1) {
         if (rb) {
             hipLaunchKernelGGL((bwd_dq_kernel<D, false, true>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
-                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, nqb, nt32);
+                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, G, nqb, nt32);
             if ((e = hipGetLastError()) != hipSuccess) return e;
             hipLaunchKernelGGL((bwd_dq_kernel<D, true, true>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
-                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, nqb, nt32);
+                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, G, nqb, nt32);
         } else {
             hipLaunchKernelGGL((bwd_dq_kernel<D, false, false>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
-                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, nqb, nt32);
+                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, G, nqb, nt32);
             if ((e = hipGetLastError()) != hipSuccess) return e;
             hipLaunchKernelGGL((bwd_dq_kernel<D, true, false>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
-                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, nqb, nt32);
+                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, G, nqb, nt32);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
         if (drb) {
@@ -817,11 +832,19 @@ hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, c
         }
     }
     if (passes & 2) {
-        hipLaunchKernelGGL((bwd_dkv_kernel<D, false>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
-                           q, k, v, dout, ca, cb, dk, dv, fk, T, BH, nkb, nt32);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL((bwd_dkv_kernel<D, true>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
-                           q, k, v, dout, ca, cb, dk, dv, fk, T, BH, nkb, nt32);
+        if (G > 1) {
+            hipLaunchKernelGGL((bwd_dkv_kernel<D, false, true>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
+                               q, k, v, dout, ca, cb, dk, dv, fk, T, BHkv, H, G, nkb, nt32);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            hipLaunchKernelGGL((bwd_dkv_kernel<D, true, true>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
+                               q, k, v, dout, ca, cb, dk, dv, fk, T, BHkv, H, G, nkb, nt32);
+        } else {
+            hipLaunchKernelGGL((bwd_dkv_kernel<D, false, false>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
+                               q, k, v, dout, ca, cb, dk, dv, fk, T, BHkv, H, G, nkb, nt32);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            hipLaunchKernelGGL((bwd_dkv_kernel<D, true, false>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
+                               q, k, v, dout, ca, cb, dk, dv, fk, T, BHkv, H, G, nkb, nt32);
+        }
         e = hipGetLastError();
     }
     return e;
@@ -840,10 +863,10 @@ size_t bwd_workspace_bytes(int B, int H, int T, int d)
 hipError_t launch_bwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
                            const float* m, const uint16_t* dout, float* dq, float* dk, float* dv,
                            float* drb, float* workspace,
-                           int B, int H, int T, int d, int passes, hipStream_t stream)
+                           int B, int H, int Hkv, int T, int d, int passes, hipStream_t stream)
 {
-    if (d == 64) return launch_one<64>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, B, H, T, passes, stream);
-    return launch_one<128>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, B, H, T, passes, stream);
+    if (d == 64) return launch_one<64>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, B, H, Hkv, T, passes, stream);
+    return launch_one<128>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, B, H, Hkv, T, passes, stream);
 }
 
 }  // namespace sb

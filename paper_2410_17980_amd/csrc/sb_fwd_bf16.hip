@@ -68,7 +68,7 @@ __global__ void __launch_bounds__(64 * NW, 2)
 fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                 const uint16_t* __restrict__ v, const uint16_t* __restrict__ rb,
                 uint16_t* __restrict__ o, float* __restrict__ m,
-                int T, int BH, int H, int nqb, float halt_carry, unsigned long long* __restrict__ tile_counts)
+                int T, int BH, int H, int G, int nqb, float halt_carry, unsigned long long* __restrict__ tile_counts)
 {
     using C = FwdCfg<D>;
     constexpr int NPW = C::NPW;
@@ -92,9 +92,11 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int hh = lane >> 5;         // half-wave: keys 16*hh .. 16*hh+15 of a subtile
     const int gg = lane >> 4, li = lane & 15;
 
+    // grouped kv heads: G consecutive query heads read the same K and V
+    const long kvh = G == 1 ? bh : (bh / H) * (H / G) + (bh % H) / G;
     const uint16_t* Qg = q + bh * (long)T * D;
-    const uint16_t* Kg = k + bh * (long)T * D;
-    const uint16_t* Vg = v + bh * (long)T * D;
+    const uint16_t* Kg = k + kvh * (long)T * D;
+    const uint16_t* Vg = v + kvh * (long)T * D;
 
     // ---- per-lane LDS byte offsets inside a 32-row subtile
     int aoff[D / 16];                       // K rows as A operand: row perm_row(n), chunk 2s + hh
@@ -393,24 +395,25 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 
 template <int D, bool WRITE_M, bool HALT, bool RB>
 hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
-                      uint16_t* o, float* m, int BH, int H, int T, float halt_carry,
+                      uint16_t* o, float* m, int BH, int H, int G, int T, float halt_carry,
                       unsigned long long* tile_counts, hipStream_t stream)
 {
     const int nqb = (T + BQ - 1) / BQ;
     const long blocks = 8L * ((BH + 7) / 8) * ((nqb + 1) / 2);
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((fwd_bf16_kernel<D, WRITE_M, HALT, RB>), dim3((unsigned)blocks), dim3(64 * NW), 0, stream,
-                       q, k, v, rb, o, m, T, BH, H, nqb, halt_carry, tile_counts);
+                       q, k, v, rb, o, m, T, BH, H, G, nqb, halt_carry, tile_counts);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
-                           uint16_t* o, float* m, int B, int H, int T, int d, hipStream_t stream)
+                           uint16_t* o, float* m, int B, int H, int Hkv, int T, int d, hipStream_t stream)
 {
     const int BH = B * H;
-#define SB_FWD(DD, WM, RBV) launch_one<DD, WM, false, RBV>(q, k, v, rb, o, m, BH, H, T, 0.0f, nullptr, stream)
+    const int G = H / Hkv;
+#define SB_FWD(DD, WM, RBV) launch_one<DD, WM, false, RBV>(q, k, v, rb, o, m, BH, H, G, T, 0.0f, nullptr, stream)
     if (d == 64) {
         if (rb) return m ? SB_FWD(64, true, true) : SB_FWD(64, false, true);
         return m ? SB_FWD(64, true, false) : SB_FWD(64, false, false);
@@ -427,8 +430,8 @@ hipError_t launch_fwd_bf16_halt(const uint16_t* q, const uint16_t* k, const uint
     const int BH = B * H;
     const float halt_carry = -log2f(eps);               // carry = -log2(stick left)
     if (d == 64)
-        return launch_one<64, false, true, false>(q, k, v, nullptr, o, nullptr, BH, H, T, halt_carry, tile_counts, stream);
-    return launch_one<128, false, true, false>(q, k, v, nullptr, o, nullptr, BH, H, T, halt_carry, tile_counts, stream);
+        return launch_one<64, false, true, false>(q, k, v, nullptr, o, nullptr, BH, H, 1, T, halt_carry, tile_counts, stream);
+    return launch_one<128, false, true, false>(q, k, v, nullptr, o, nullptr, BH, H, 1, T, halt_carry, tile_counts, stream);
 }
 
 }  // namespace sb

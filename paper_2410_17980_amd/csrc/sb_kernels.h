@@ -12,9 +12,10 @@ namespace sb {
 hipError_t launch_fwd_f32(const float* q, const float* k, const float* v, float* o, float* m,
                           int B, int H, int T, int d, hipStream_t stream);
 
-// rb: remainder-bias embeddings [H][d] bf16, or nullptr; m: nullptr when not wanted
+// rb: remainder-bias embeddings [H][d] bf16, or nullptr; m: nullptr when not wanted.
+// H query heads, Hkv kv heads (H a multiple of Hkv): k, v are [B][Hkv][T][d].
 hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
-                           uint16_t* o, float* m, int B, int H, int T, int d, hipStream_t stream);
+                           uint16_t* o, float* m, int B, int H, int Hkv, int T, int d, hipStream_t stream);
 
 // forward that stops sweeping a query block once every row has less than eps of its stick left
 hipError_t launch_fwd_bf16_halt(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o,
@@ -25,11 +26,12 @@ hipError_t launch_fwd_bf16_halt(const uint16_t* q, const uint16_t* k, const uint
 // passes: bit 0 = query-stationary pass (dq and the carries in the workspace; with rb
 // also drb [H][d]), bit 1 = key-stationary pass (dk, dv from the carries).
 // rb, drb: remainder-bias embeddings and their gradient, both nullptr without the bias.
+// H query heads, Hkv kv heads: k, v, dk, dv are [B][Hkv][T][d].
 size_t bwd_workspace_bytes(int B, int H, int T, int d);
 hipError_t launch_bwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
                            const float* m, const uint16_t* dout, float* dq, float* dk, float* dv,
                            float* drb, float* workspace,
-                           int B, int H, int T, int d, int passes, hipStream_t stream);
+                           int B, int H, int Hkv, int T, int d, int passes, hipStream_t stream);
 
 // MFMA-only diagnostic: operands = at least 1 MiB of bf16 on the device, ticks = 3 x u64 on the device
 hipError_t launch_diag_mfma(const void* operands, int iters, unsigned long long* ticks, hipStream_t stream);
