@@ -15,7 +15,7 @@
  *   - All tensor pointers are DEVICE pointers owned by the caller; the library
  *     never allocates, frees or keeps device memory and holds no state.
  *   - Layout [B, H, T, d], contiguous, d fastest.  `m` is [B, H, T].
- *   - d is 64 or 128; B, H, T >= 1 (any T, not only multiples of the tile);
+ *   - d is 32, 64 or 128; B, H, T >= 1 (any T, not only multiples of the tile);
  *     B*H*T*d must be below 2^40 elements.
  *   - Every tensor pointer must be 16-byte aligned.
  *   - `stream` is a hipStream_t passed as void*; NULL means the default stream.
@@ -37,7 +37,7 @@ typedef enum {
     SB_OK = 0,
     SB_ERR_NULL = -1,        /* a required pointer is NULL */
     SB_ERR_SHAPE = -2,       /* B, H or T < 1, or the tensor is too large */
-    SB_ERR_UNSUPPORTED = -3, /* d is not 64 or 128 */
+    SB_ERR_UNSUPPORTED = -3, /* d is not 32, 64 or 128 */
     SB_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
     SB_ERR_LAUNCH = -5,      /* the HIP launch reported an error */
     SB_ERR_WORKSPACE = -6    /* workspace missing or too small */

@@ -10,7 +10,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 int check_shape(int B, int H, int T, int d)
 {
     if (B < 1 || H < 1 || T < 1) return SB_ERR_SHAPE;
-    if (d != 64 && d != 128) return SB_ERR_UNSUPPORTED;
+    if (d != 32 && d != 64 && d != 128) return SB_ERR_UNSUPPORTED;
     const double elems = (double)B * H * (double)T * d;
     if (elems >= 1099511627776.0 /* 2^40 */ || (double)B * H > 2147483647.0) return SB_ERR_SHAPE;
     return SB_OK;
@@ -189,7 +189,7 @@ const char* sb_status_string(int status)
     case SB_OK: return "ok";
     case SB_ERR_NULL: return "null pointer";
     case SB_ERR_SHAPE: return "bad shape";
-    case SB_ERR_UNSUPPORTED: return "unsupported head dimension (need 64 or 128)";
+    case SB_ERR_UNSUPPORTED: return "unsupported head dimension (need 32, 64 or 128)";
     case SB_ERR_ALIGN: return "pointer not 16-byte aligned";
     case SB_ERR_LAUNCH: return "kernel launch failed";
     case SB_ERR_WORKSPACE: return "workspace missing or too small";

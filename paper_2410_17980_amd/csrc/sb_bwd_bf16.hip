@@ -865,6 +865,7 @@ hipError_t launch_bwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t*
                            float* drb, float* workspace,
                            int B, int H, int Hkv, int T, int d, int passes, hipStream_t stream)
 {
+    if (d == 32) return launch_one<32>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, B, H, Hkv, T, passes, stream);
     if (d == 64) return launch_one<64>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, B, H, Hkv, T, passes, stream);
     return launch_one<128>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, B, H, Hkv, T, passes, stream);
 }

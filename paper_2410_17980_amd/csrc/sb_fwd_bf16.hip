@@ -414,6 +414,10 @@ hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t*
     const int BH = B * H;
     const int G = H / Hkv;
 #define SB_FWD(DD, WM, RBV) launch_one<DD, WM, false, RBV>(q, k, v, rb, o, m, BH, H, G, T, 0.0f, nullptr, stream)
+    if (d == 32) {
+        if (rb) return m ? SB_FWD(32, true, true) : SB_FWD(32, false, true);
+        return m ? SB_FWD(32, true, false) : SB_FWD(32, false, false);
+    }
     if (d == 64) {
         if (rb) return m ? SB_FWD(64, true, true) : SB_FWD(64, false, true);
         return m ? SB_FWD(64, true, false) : SB_FWD(64, false, false);
@@ -429,6 +433,8 @@ hipError_t launch_fwd_bf16_halt(const uint16_t* q, const uint16_t* k, const uint
 {
     const int BH = B * H;
     const float halt_carry = -log2f(eps);               // carry = -log2(stick left)
+    if (d == 32)
+        return launch_one<32, false, true, false>(q, k, v, nullptr, o, nullptr, BH, H, 1, T, halt_carry, tile_counts, stream);
     if (d == 64)
         return launch_one<64, false, true, false>(q, k, v, nullptr, o, nullptr, BH, H, 1, T, halt_carry, tile_counts, stream);
     return launch_one<128, false, true, false>(q, k, v, nullptr, o, nullptr, BH, H, 1, T, halt_carry, tile_counts, stream);

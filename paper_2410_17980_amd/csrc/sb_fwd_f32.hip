@@ -115,7 +115,9 @@ hipError_t launch_fwd_f32(const float* q, const float* k, const float* v, float*
     const long blocks = (long)B * H * nqb;
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(F32_BQ);
-    if (d == 64)
+    if (d == 32)
+        hipLaunchKernelGGL(fwd_f32_kernel<32>, grid, block, 0, stream, q, k, v, o, m, T, nqb);
+    else if (d == 64)
         hipLaunchKernelGGL(fwd_f32_kernel<64>, grid, block, 0, stream, q, k, v, o, m, T, nqb);
     else
         hipLaunchKernelGGL(fwd_f32_kernel<128>, grid, block, 0, stream, q, k, v, o, m, T, nqb);

@@ -44,15 +44,21 @@ __device__ __forceinline__ int perm_row(int rho)
 //       and the two quarter-waves of a half-wave the other 32 B of the same 64 B.
 // swz_perm is for tiles whose operand reads go through perm_row (the 16 rows are
 // {0..7, 16..23} + 8k), swz_nat for tiles read in natural row order (rows 0..15 + 16k).
+// A row holds D/8 chunks (16 at D = 128, 8 at D = 64, 4 at D = 32), so 1, 2 or 4 rows
+// share the 64 banks and the xor needs 4, 3 or 2 bits.
 template <int D> __device__ __forceinline__ int swz_perm(int row)
 {
+    static_assert(D == 32 || D == 64 || D == 128, "head dimension");
     if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 1) | (((row >> 4) & 1) << 1);
-    return (((row >> 1) & 1) << 2) | ((row >> 2) & 1) | (((row >> 4) & 1) << 1);
+    if (D == 64) return (((row >> 1) & 1) << 2) | ((row >> 2) & 1) | (((row >> 4) & 1) << 1);
+    return ((row >> 2) & 1) | (((row >> 4) & 1) << 1);
 }
 template <int D> __device__ __forceinline__ int swz_nat(int row)
 {
+    static_assert(D == 32 || D == 64 || D == 128, "head dimension");
     if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
-    return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+    if (D == 64) return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+    return (row >> 2) & 3;
 }
 
 // byte offset of 16-byte chunk c of tile row `row`

@@ -59,7 +59,7 @@ def test_argument_validation_without_a_gpu(lib):
     assert lib.sb_attn_fwd_f32(p, p, None, p, None, 1, 1, 8, 64, None) == -1
     assert lib.sb_attn_fwd_f32(p, p, p, p, odd, 1, 1, 8, 64, None) == -4
     assert lib.sb_attn_bwd(p, p, p, None, p, p, p, p, None, 0, 1, 1, 8, 64, None) == -1
-    assert lib.sb_attn_bwd(p, p, p, p, p, p, p, p, None, 0, 1, 1, 8, 32, None) == -3
+    assert lib.sb_attn_bwd(p, p, p, p, p, p, p, p, None, 0, 1, 1, 8, 48, None) == -3
     # remainder bias: r and dr are required
     assert lib.sb_attn_fwd_rb(p, p, p, None, p, None, 1, 1, 8, 64, None) == -1
     assert lib.sb_attn_fwd_rb(p, p, p, odd, p, None, 1, 1, 8, 64, None) == -4

@@ -56,13 +56,13 @@ def check(sb, oracle, q, k, v, g):
 
 
 @pytest.mark.parametrize("T", [1, 2, 32, 33, 64, 100, 129, 300])
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_bwd_shapes(sb, oracle, gen, T, d):
     q, k, v, g = gen.gaussian(2, 3, T, d, seed=300 + T + d, dtype="bf16", with_dout=True)
     check(sb, oracle, q, k, v, g)
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_bwd_finite_differences_T32(sb, oracle, gen, d):
     """Directional finite differences of the float64 forward at T = 32 against
     the GPU gradients (independent of the oracle's own backward)."""
@@ -81,10 +81,10 @@ def test_bwd_finite_differences_T32(sb, oracle, gen, d):
         assert abs(fd - an) <= 2e-3 * norm + 1e-3, (fd, an)
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_bwd_long_range(sb, oracle, gen, d):
     """Slowly decaying weights: the carries a and b cross many key tiles."""
-    kval = -48.0 if d == 64 else -64.0
+    kval = {32: -34.0, 64: -48.0, 128: -64.0}[d]          # logit about -6
     q, k, v, g = gen.constant_logit(1, 2, 700, d, seed=13, kval=kval, dtype="bf16", with_dout=True)
     check(sb, oracle, q, k, v, g)
     q, k, v, g = gen.biased_gaussian(1, 2, 700, d, seed=14, shift=-6.0, dtype="bf16", with_dout=True)

@@ -60,7 +60,7 @@ def test_f32_workload_1(sb, oracle, gen):
 
 
 @pytest.mark.parametrize("T", [1, 2, 31, 64, 65, 200, 257])
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_f32_shapes(sb, oracle, gen, T, d):
     q, k, v = gen.gaussian(2, 3, T, d, seed=100 + T, dtype="f32")
     qd, kd, vd = dev(q, k, v)
@@ -85,13 +85,13 @@ def test_f32_long_range_and_sharp(sb, oracle, gen):
 
 # ------------------------------------------------------------------ bf16 path
 @pytest.mark.parametrize("T", [1, 2, 31, 32, 33, 64, 100, 127, 128, 129, 300, 517])
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_bf16_shapes(sb, oracle, gen, T, d):
     q, k, v = gen.gaussian(2, 3, T, d, seed=200 + T + d, dtype="bf16")
     run_bf16(sb, oracle, q, k, v)
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_bf16_first_row_is_zero_and_deterministic(sb, gen, d):
     q, k, v = dev(*gen.gaussian(3, 5, 333, d, seed=9, dtype="bf16"))
     o1, m1 = sb.sb_attn_fwd_train(q, k, v)
@@ -101,12 +101,12 @@ def test_bf16_first_row_is_zero_and_deterministic(sb, gen, d):
     assert not o1[:, :, 0].any() and not m1[:, :, 0].any()
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_bf16_constant_logit_long_range(sb, oracle, gen, d):
     """Small equal sigma everywhere: weights reach across many key tiles, so a
     wrong cross-tile carry cannot hide.  Closed form: A = b (1-b)^(j-i-1)."""
     T = 1100
-    kval = -48.0 if d == 64 else -64.0
+    kval = {32: -34.0, 64: -48.0, 128: -64.0}[d]          # logit about -6
     q, k, v = gen.constant_logit(1, 2, T, d, seed=3, kval=kval, dtype="bf16")
     run_bf16(sb, oracle, q, k, v)
     # and directly against the closed form, independent of the oracle
@@ -117,7 +117,7 @@ def test_bf16_constant_logit_long_range(sb, oracle, gen, d):
     assert max_abs(o[0, 0], A @ to64(v)[0, 0]) <= BF16_TOL
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_bf16_biased_long_range(sb, oracle, gen, d):
     q, k, v = gen.biased_gaussian(1, 3, 900, d, seed=4, shift=-6.0, dtype="bf16")
     run_bf16(sb, oracle, q, k, v)
@@ -196,11 +196,11 @@ def test_halt_matches_oracle_and_skips_tiles(sb, oracle, gen):
     assert 0 < swept < 0.35 * full
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_halt_never_triggers_on_slowly_decaying_weights(sb, gen, d):
     """Constant small logit: the stick is far from used up at T = 700, nothing may be skipped
     and the result is bit-identical to the plain forward."""
-    kval = -48.0 if d == 64 else -64.0
+    kval = {32: -34.0, 64: -48.0, 128: -64.0}[d]          # logit about -6
     q, k, v = dev(*gen.constant_logit(1, 2, 700, d, seed=32, kval=kval, dtype="bf16"))
     counts = torch.zeros(2, dtype=torch.int64, device="cuda")
     o1 = sb.sb_attn_fwd(q, k, v)

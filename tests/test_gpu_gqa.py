@@ -61,7 +61,7 @@ def check(sb, oracle, q, k, v, g, r=None):
 
 
 @pytest.mark.parametrize("H,Hkv", [(4, 2), (6, 2), (12, 4), (3, 1), (2, 2)])
-@pytest.mark.parametrize("T,d", [(100, 64), (300, 128)])
+@pytest.mark.parametrize("T,d", [(100, 64), (300, 128), (200, 32)])
 def test_groups(sb, oracle, gen, H, Hkv, T, d):
     check(sb, oracle, *make(gen, 2, H, Hkv, T, d, seed=H * 10 + Hkv))
 

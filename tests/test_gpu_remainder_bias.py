@@ -62,13 +62,13 @@ def check_bwd(sb, oracle, q, k, v, r, g):
 
 
 @pytest.mark.parametrize("T", [1, 2, 33, 64, 129, 300])
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_shapes(sb, oracle, gen, T, d):
     q, k, v, g = gen.gaussian(2, 3, T, d, seed=100 + T + d, with_dout=True)
     check_bwd(sb, oracle, q, k, v, gen.remainder_embedding(3, d, seed=7), g)
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_large_remainder_across_tiles(sb, oracle, gen, d):
     """Logits around -6: most of the stick is left over for hundreds of keys, so the
     remainder term dominates o and the gradient of the logits."""
