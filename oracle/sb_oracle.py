@@ -152,3 +152,46 @@ def bwd_gqa(q, k, v, dout, r=None):
     dk = out[1].reshape(B, Hkv, H // Hkv, T, d).sum(axis=2)
     dv = out[2].reshape(B, Hkv, H // Hkv, T, d).sum(axis=2)
     return (out[0], dk, dv) + tuple(out[3:])
+
+
+def _seq_bounds(cu_seqlens, Ttot):
+    cu = [int(x) for x in cu_seqlens]
+    assert len(cu) >= 1 and cu[0] == 0 and cu[-1] == Ttot, "cu_seqlens must run from 0 to the packed length"
+    assert all(a <= b for a, b in zip(cu, cu[1:])), "cu_seqlens must not decrease"
+    return list(zip(cu, cu[1:]))
+
+
+def fwd_varlen(q, k, v, cu_seqlens, r=None):
+    """Packed variable-length batch (padding-free training, section 5 set-up): q [H,Ttot,d],
+    k, v [Hkv,Ttot,d] hold the sequences one after the other along T; sequence s occupies
+    rows cu_seqlens[s] .. cu_seqlens[s+1]-1 and attends only inside itself.  Plain
+    definition: Eq. 1 on every sequence separately.  Returns (o [H,Ttot,d], rem [H,Ttot])."""
+    q = np.asarray(q, dtype=np.float64)
+    H, Ttot, d = q.shape
+    o = np.zeros((H, Ttot, d))
+    rem = np.ones((H, Ttot))
+    for a, b in _seq_bounds(cu_seqlens, Ttot):
+        if b > a:
+            os_, rs = fwd_gqa(q[None, :, a:b], np.asarray(k)[None, :, a:b], np.asarray(v)[None, :, a:b], r=r)
+            o[:, a:b] = os_[0]
+            rem[:, a:b] = rs[0]
+    return o, rem
+
+
+def bwd_varlen(q, k, v, dout, cu_seqlens, r=None):
+    """Gradients of fwd_varlen: every sequence on its own; dr adds up over the sequences."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    H, Ttot, d = q.shape
+    dq = np.zeros(q.shape)
+    dk = np.zeros(k.shape)
+    dv = np.zeros(k.shape)
+    dr = np.zeros((H, d)) if r is not None else None
+    for a, b in _seq_bounds(cu_seqlens, Ttot):
+        if b > a:
+            out = bwd_gqa(q[None, :, a:b], k[None, :, a:b], np.asarray(v)[None, :, a:b],
+                          np.asarray(dout)[None, :, a:b], r=r)
+            dq[:, a:b], dk[:, a:b], dv[:, a:b] = out[0][0], out[1][0], out[2][0]
+            if r is not None:
+                dr += out[3].reshape(H, d)
+    return (dq, dk, dv, dr) if r is not None else (dq, dk, dv)
