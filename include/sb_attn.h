@@ -152,6 +152,31 @@ int sb_attn_bwd_gqa(const void* q, const void* k, const void* v, const void* r, 
                     void* workspace, size_t workspace_bytes, int B, int H, int Hkv, int T, int d, void* stream);
 
 /*
+ * Packed variable-length batches (the paper trains padding-free): the sequences of a batch
+ * lie one after the other along T and attend only inside themselves.
+ * q, o, dout, dq: [H, Ttot, d]; k, v, dk, dv: [Hkv, Ttot, d]; m: [H, Ttot] fp32;
+ * r (optional), dr: [H, d].  cu_seqlens: nseq + 1 ints on the DEVICE, cu[0] = 0,
+ * non-decreasing, cu[nseq] = Ttot; sequence s is rows cu[s] .. cu[s+1]-1 (empty
+ * sequences allowed).  max_T: an upper bound of the longest sequence, 1 <= max_T <= Ttot;
+ * it sizes the launch and the workspace, so a tight bound is cheaper.  The library cannot
+ * read cu_seqlens on the host: rows of a sequence beyond max_T, or beyond Ttot, are left
+ * unwritten rather than touched out of bounds; other malformed offsets give undefined
+ * values in o / the gradients of the affected sequences.
+ * The first row of every sequence has nothing to attend to (o = 0, or r with the bias).
+ * Otherwise exactly sb_attn_fwd_gqa / sb_attn_bwd_gqa per sequence, in one launch each;
+ * dr adds up over all sequences in a fixed order.
+ * Workspace: sb_attn_varlen_bwd_workspace_bytes(nseq, H, Ttot, max_T, d) bytes
+ * = 8*H*Ttot*ceil(max_T/32) + nseq*H*(8 + 4*d)*ceil(max_T/128).
+ */
+int sb_attn_varlen_fwd(const void* q, const void* k, const void* v, const void* r, void* o, float* m,
+                       const int* cu_seqlens, int nseq, int H, int Hkv, int Ttot, int max_T, int d, void* stream);
+size_t sb_attn_varlen_bwd_workspace_bytes(int nseq, int H, int Ttot, int max_T, int d);
+int sb_attn_varlen_bwd(const void* q, const void* k, const void* v, const void* r, const float* m,
+                       const void* dout, float* dq, float* dk, float* dv, float* dr,
+                       const int* cu_seqlens, int nseq, int H, int Hkv, int Ttot, int max_T, int d,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Measurement aid (not part of the method): runs `iters` x 16 independent
  * 32x32x16 bf16 MFMAs per wavefront, two wavefronts per SIMD on the whole chip,
  * on operands taken from `operands` (device, bf16, at least 1 MiB, 16-byte

@@ -18,6 +18,7 @@ EXPORTS = (
     "sb_attn_fwd", "sb_attn_fwd_halt", "sb_attn_fwd_train", "sb_attn_fwd_f32",
     "sb_attn_bwd_workspace_bytes", "sb_attn_bwd", "sb_attn_bwd_dq", "sb_attn_bwd_dkdv",
     "sb_attn_fwd_rb", "sb_attn_bwd_rb", "sb_attn_fwd_gqa", "sb_attn_bwd_gqa",
+    "sb_attn_varlen_fwd", "sb_attn_varlen_bwd_workspace_bytes", "sb_attn_varlen_bwd",
     "sb_diag_mfma_rate",
     "sb_status_string", "sb_version",
 )
@@ -66,6 +67,13 @@ def load(build_if_missing: bool = True):
     lib.sb_attn_bwd_gqa.argtypes = [vp, vp, vp, vp, fp, vp, fp, fp, fp, fp, vp, ctypes.c_size_t,
                                     ci, ci, ci, ci, ci, vp]
     lib.sb_attn_bwd_gqa.restype = ci
+    lib.sb_attn_varlen_fwd.argtypes = [vp, vp, vp, vp, vp, fp, vp, ci, ci, ci, ci, ci, ci, vp]
+    lib.sb_attn_varlen_fwd.restype = ci
+    lib.sb_attn_varlen_bwd_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.sb_attn_varlen_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.sb_attn_varlen_bwd.argtypes = [vp, vp, vp, vp, fp, vp, fp, fp, fp, fp, vp, ci, ci, ci, ci, ci, ci,
+                                       vp, ctypes.c_size_t, vp]
+    lib.sb_attn_varlen_bwd.restype = ci
     lib.sb_diag_mfma_rate.argtypes = [vp, ctypes.c_size_t, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.sb_diag_mfma_rate.restype = ci
     lib.sb_status_string.argtypes = [ci]
@@ -267,6 +275,66 @@ def sb_attn_bwd_gqa(q, k, v, m, dout, r=None, dq=None, dk=None, dv=None, dr=None
                                 _ptr(dv, torch.float32, kv_shape, "dv"), _ptr(dr, torch.float32, (H, d), "dr"),
                                 ws_ptr, ws_bytes, B, H, Hkv, T, d, _stream(stream))
     _check(rc, "sb_attn_bwd_gqa")
+    return (dq, dk, dv, dr) if r is not None else (dq, dk, dv)
+
+
+def _dims3(t, name):
+    if t.dim() != 3:
+        raise SbAttnError(f"{name}: expected a packed [H, Ttot, d] tensor")
+    return tuple(int(x) for x in t.shape)
+
+
+def sb_attn_varlen_fwd(q, k, v, cu_seqlens, max_T, r=None, o=None, m=None, want_m=True, stream=None):
+    """bf16 forward on a packed variable-length batch: q [H,Ttot,d], k, v [Hkv,Ttot,d],
+    cu_seqlens int32 [nseq+1] on the GPU, max_T >= the longest sequence.  Returns (o, m) or o."""
+    H, Ttot, d = _dims3(q, "q")
+    Hkv = _dims3(k, "k")[0]
+    nseq = int(cu_seqlens.numel()) - 1
+    if o is None:
+        o = torch.empty_like(q)
+    if m is None and want_m:
+        m = torch.empty((H, Ttot), dtype=torch.float32, device=q.device)
+    kv_shape = (Hkv, Ttot, d)
+    rc = load().sb_attn_varlen_fwd(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, kv_shape, "k"),
+                                   _ptr(v, torch.bfloat16, kv_shape, "v"), _ptr(r, torch.bfloat16, (H, d), "r"),
+                                   _ptr(o, torch.bfloat16, q.shape, "o"), _ptr(m, torch.float32, (H, Ttot), "m"),
+                                   _ptr(cu_seqlens, torch.int32, None, "cu_seqlens"),
+                                   nseq, H, Hkv, Ttot, int(max_T), d, _stream(stream))
+    _check(rc, "sb_attn_varlen_fwd")
+    return (o, m) if m is not None else o
+
+
+def sb_attn_varlen_bwd_workspace_bytes(nseq, H, Ttot, max_T, d) -> int:
+    return int(load().sb_attn_varlen_bwd_workspace_bytes(nseq, H, Ttot, max_T, d))
+
+
+def sb_attn_varlen_bwd(q, k, v, m, dout, cu_seqlens, max_T, r=None, dq=None, dk=None, dv=None, dr=None,
+                       workspace=None, stream=None):
+    """bf16 backward on a packed variable-length batch.  Returns (dq, dk, dv[, dr]) in fp32."""
+    H, Ttot, d = _dims3(q, "q")
+    Hkv = _dims3(k, "k")[0]
+    nseq = int(cu_seqlens.numel()) - 1
+    kv_shape = (Hkv, Ttot, d)
+    mk = lambda shape: torch.empty(shape, dtype=torch.float32, device=q.device)
+    dq = mk(q.shape) if dq is None else dq
+    dk = mk(kv_shape) if dk is None else dk
+    dv = mk(kv_shape) if dv is None else dv
+    if r is not None and dr is None:
+        dr = mk((H, d))
+    need = sb_attn_varlen_bwd_workspace_bytes(nseq, H, Ttot, int(max_T), d)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_ptr = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = load().sb_attn_varlen_bwd(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, kv_shape, "k"),
+                                   _ptr(v, torch.bfloat16, kv_shape, "v"), _ptr(r, torch.bfloat16, (H, d), "r"),
+                                   _ptr(m, torch.float32, (H, Ttot), "m"),
+                                   _ptr(dout, torch.bfloat16, q.shape, "dout"),
+                                   _ptr(dq, torch.float32, q.shape, "dq"), _ptr(dk, torch.float32, kv_shape, "dk"),
+                                   _ptr(dv, torch.float32, kv_shape, "dv"), _ptr(dr, torch.float32, (H, d), "dr"),
+                                   _ptr(cu_seqlens, torch.int32, None, "cu_seqlens"),
+                                   nseq, H, Hkv, Ttot, int(max_T), d, ws_ptr, ws_bytes, _stream(stream))
+    _check(rc, "sb_attn_varlen_bwd")
     return (dq, dk, dv, dr) if r is not None else (dq, dk, dv)
 
 

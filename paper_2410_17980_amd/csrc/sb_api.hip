@@ -172,6 +172,58 @@ int sb_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* do
                        B, H, H, T, d, 2, stream);
 }
 
+namespace {
+int check_varlen(int nseq, int H, int Hkv, int Ttot, int max_T, int d)
+{
+    if (nseq < 1 || H < 1 || Hkv < 1 || H % Hkv != 0 || Ttot < 1 || max_T < 1 || max_T > Ttot) return SB_ERR_SHAPE;
+    if (d != 32 && d != 64 && d != 128) return SB_ERR_UNSUPPORTED;
+    if ((double)H * Ttot * d >= 1099511627776.0 || (double)nseq * H > 2147483647.0) return SB_ERR_SHAPE;
+    return SB_OK;
+}
+}  // namespace
+
+int sb_attn_varlen_fwd(const void* q, const void* k, const void* v, const void* r, void* o, float* m,
+                       const int* cu_seqlens, int nseq, int H, int Hkv, int Ttot, int max_T, int d, void* stream)
+{
+    if (!q || !k || !v || !o || !cu_seqlens) return SB_ERR_NULL;
+    if (int rc = check_varlen(nseq, H, Hkv, Ttot, max_T, d)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(r) || !aligned16(o) || !aligned16(m))
+        return SB_ERR_ALIGN;
+    hipError_t e = sb::launch_fwd_bf16_varlen(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                                              static_cast<const uint16_t*>(v), static_cast<const uint16_t*>(r),
+                                              static_cast<uint16_t*>(o), m, cu_seqlens, nseq, H, Hkv, Ttot, max_T, d,
+                                              static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
+size_t sb_attn_varlen_bwd_workspace_bytes(int nseq, int H, int Ttot, int max_T, int d)
+{
+    if (check_varlen(nseq, H, H, Ttot, max_T, d) != SB_OK) return 0;
+    return sb::bwd_varlen_workspace_bytes(nseq, H, Ttot, max_T, d);
+}
+
+int sb_attn_varlen_bwd(const void* q, const void* k, const void* v, const void* r, const float* m,
+                       const void* dout, float* dq, float* dk, float* dv, float* dr,
+                       const int* cu_seqlens, int nseq, int H, int Hkv, int Ttot, int max_T, int d,
+                       void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !m || !dout || !dq || !dk || !dv || !cu_seqlens) return SB_ERR_NULL;
+    if ((r == nullptr) != (dr == nullptr)) return SB_ERR_NULL;
+    if (int rc = check_varlen(nseq, H, Hkv, Ttot, max_T, d)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(m) || !aligned16(dout) ||
+        !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(workspace) ||
+        !aligned16(r) || !aligned16(dr))
+        return SB_ERR_ALIGN;
+    if (!workspace || workspace_bytes < sb::bwd_varlen_workspace_bytes(nseq, H, Ttot, max_T, d))
+        return SB_ERR_WORKSPACE;
+    hipError_t e = sb::launch_bwd_bf16_varlen(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                                              static_cast<const uint16_t*>(v), static_cast<const uint16_t*>(r), m,
+                                              static_cast<const uint16_t*>(dout), dq, dk, dv, dr,
+                                              static_cast<float*>(workspace), cu_seqlens, nseq, H, Hkv,
+                                              Ttot, max_T, d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
 int sb_diag_mfma_rate(const void* operands, size_t operand_bytes, int iters, unsigned long long* ticks,
                       double* flop, void* stream)
 {

@@ -233,14 +233,19 @@ __device__ __forceinline__ void stage_tile(const uint16_t* X, const uint16_t* Y,
 }
 
 // ------------------------------------------------------------------ dQ kernel
-template <int D, bool SLOW, bool RB>
+// VL (both kernels): packed variable-length batch, tensors [H][Ttot][D] ([H/G][Ttot][D] for
+// k, v, dk, dv) with sequence s at rows cu[s] .. cu[s+1]-1.  BH counts (sequence, head)
+// pairs; T_arg and the block counts describe the longest sequence (they size the grid, the
+// flag arrays and the carries, which are then laid out [head][strip][Ttot]); a workgroup
+// whose blocks lie beyond its own sequence's end returns at once.
+template <int D, bool SLOW, bool RB, bool VL>
 __global__ void __launch_bounds__(NTHREADS, SLOW ? 1 : 2)
 bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
               const uint16_t* __restrict__ v, const uint16_t* __restrict__ rb,
               const float* __restrict__ m,
               const uint16_t* __restrict__ dout, float* __restrict__ dq,
               float* __restrict__ ca, float* __restrict__ cb, int* __restrict__ flags,
-              int T, int BH, int H, int G, int nqb, int nt32)
+              int T_arg, int BH, int H, int G, int nqb_arg, int nt32, const int* __restrict__ cu, int Ttot)
 {
     using C = StageCfg<D>;
     __shared__ __attribute__((aligned(1024))) char smem[2 * C::STAGE];
@@ -248,10 +253,33 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 
     const int wg = blockIdx.x;
     const int xcd = wg & 7, slot = wg >> 3;
-    const int npair = (nqb + 1) >> 1;
+    const int npair = (nqb_arg + 1) >> 1;
     const long bh = xcd + 8L * (slot / npair);
     const int pidx = slot % npair;
     if (bh >= BH) return;
+    int T = T_arg, nqb = nqb_arg;
+    long row0, kvrow0, cbase, cstride;      // first q / k row of this head; carries: base and strip stride
+    int head;
+    if constexpr (VL) {
+        const int seq = (int)(bh / H);
+        head = (int)(bh % H);
+        const int c0 = cu[seq];
+        T = min(min(cu[seq + 1], Ttot) - c0, T_arg);      // never past the packed rows or the stated maximum
+        if (c0 < 0) return;
+        nqb = (T + BQ - 1) / BQ;
+        if (pidx >= ((nqb + 1) >> 1)) return;
+        row0 = (long)head * Ttot + c0;
+        kvrow0 = (long)(head / G) * Ttot + c0;
+        cbase = (long)head * nt32 * Ttot + c0;
+        cstride = Ttot;
+    } else {
+        // grouped kv heads: G consecutive query heads read the same K and V
+        head = (int)(bh % H);
+        row0 = bh * (long)T;
+        kvrow0 = (G == 1 ? bh : (bh / H) * (H / G) + (bh % H) / G) * (long)T;
+        cbase = bh * (long)nt32 * T;
+        cstride = T;
+    }
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -259,9 +287,8 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int n = lane & 31, hh = lane >> 5;
     const int gg = lane >> 4, li = lane & 15;
 
-    const long base = bh * (long)T * D;
-    // grouped kv heads: G consecutive query heads read the same K and V
-    const long kvbase = (G == 1 ? bh : (bh / H) * (H / G) + (bh % H) / G) * (long)T * D;
+    const long base = row0 * D;
+    const long kvbase = kvrow0 * D;
     const uint16_t* Kg = k + kvbase;
     const uint16_t* Vg = v + kvbase;
 
@@ -287,8 +314,8 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 
     const float scale = 1.0f / sqrtf((float)D);
     const float c2 = SB_LOG2E * scale;
-    float* const cag = ca + bh * (long)nt32 * T;
-    float* const cbg = cb + bh * (long)nt32 * T;
+    float* const cag = ca + cbase;
+    float* const cbg = cb + cbase;
 
     bf16x8 qf[D / 16], gf[D / 16];          // B operands: this lane's query row of Q and dO
     f32x16 dqacc[D / 32];
@@ -341,7 +368,7 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         }
         // carries of this (subtile, query) for the key-stationary kernel
         if (hh == 0 && q0 + n < T) {
-            const long ci = (long)(key0 >> 5) * T + q0 + n;
+            const long ci = (long)(key0 >> 5) * cstride + q0 + n;
             cag[ci] = so.ca_right;
             cbg[ci] = bsum;
         }
@@ -366,7 +393,7 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     for (int part = 0; part < 2; ++part) {
         const int qb = part == 0 ? nqb - 1 - pidx : pidx;
         if (part == 1 && 2 * pidx == nqb - 1) break;     // odd block count: the middle block is alone
-        if (SLOW && flags[bh * nqb + qb] == 0) continue;  // only the blocks the fast variant flagged
+        if (SLOW && flags[bh * nqb_arg + qb] == 0) continue;  // only the blocks the fast variant flagged
         const int Q0 = qb * BQ;
         q0 = Q0 + wave * 32;
         const bool wave_live = q0 < T;
@@ -385,13 +412,13 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                 gf[s] = __builtin_bit_cast(bf16x8, g);
             }
         }
-        a2 = -m[bh * (long)T + jq] * SB_LOG2E;
+        a2 = -m[row0 + jq] * SB_LOG2E;
         bsum = 0.0f;
         if constexpr (RB) {
             // remainder bias (Appendix C): the unused stick exp(m) acts like one more weight
             // in front of key 0, with "value" r_head: the cumulative sum of G starts at
             // exp(m_j) (dO_j . r_head)
-            const u32x4* rs = reinterpret_cast<const u32x4*>(rb + (bh % H) * D + 8 * hh);
+            const u32x4* rs = reinterpret_cast<const u32x4*>(rb + head * D + 8 * hh);
             float dot = 0.0f;
 #pragma unroll
             for (int s = 0; s < D / 16; ++s) {
@@ -461,7 +488,7 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         if constexpr (!SLOW) {
             if (__builtin_amdgcn_ballot_w64(dirty) != 0 && lane == 0) atomicOr(&s_dirty, 1);
             __syncthreads();
-            if (tid == 0) flags[bh * nqb + qb] = s_dirty;
+            if (tid == 0) flags[bh * nqb_arg + qb] = s_dirty;
         }
     }
 }
@@ -473,13 +500,13 @@ template <int D> struct DkvCfg {
     static constexpr int LDS_BYTES = T_OFF + NW * T_WAVE;
 };
 
-template <int D, bool SLOW, bool GQA>
+template <int D, bool SLOW, bool GQA, bool VL>
 __global__ void __launch_bounds__(NTHREADS, 1)
 bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                const uint16_t* __restrict__ v, const uint16_t* __restrict__ dout,
                const float* __restrict__ ca, const float* __restrict__ cb,
                float* __restrict__ dk, float* __restrict__ dv, int* __restrict__ flags,
-               int T, int BH, int H, int G_arg, int nkb, int nt32)
+               int T_arg, int BH, int H, int G_arg, int nkb_arg, int nt32, const int* __restrict__ cu, int Ttot)
 {
     using C = StageCfg<D>;
     using CK = DkvCfg<D>;
@@ -489,7 +516,7 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 
     const int wg = blockIdx.x;
     const int xcd = wg & 7, slot = wg >> 3;
-    const int npair = (nkb + 1) >> 1;
+    const int npair = (nkb_arg + 1) >> 1;
     const long bh = xcd + 8L * (slot / npair);
     const int pidx = slot % npair;
     if (bh >= BH) return;
@@ -501,9 +528,34 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int gg = lane >> 4, li = lane & 15;
 
     // bh counts kv heads here (BH = B * H / G of them); its G query heads are qh0 .. qh0+G-1
-    const long base = bh * (long)T * D;
     const int Hkv = H / G;
-    const long qh0 = G == 1 ? bh : (bh / Hkv) * H + (bh % Hkv) * G;
+    int T = T_arg, nkb = nkb_arg;
+    long base;                              // first element of this kv head's K / V / dK / dV rows
+    long qrow0, qrow_step;                  // first Q / dO row of query head qh0, step to the next head
+    long cbase, cbase_step, cstride;        // carries: start for head qh0, step per head, strip stride
+    if constexpr (VL) {
+        const int seq = (int)(bh / Hkv);
+        const int hkv = (int)(bh % Hkv);
+        const int c0 = cu[seq];
+        T = min(min(cu[seq + 1], Ttot) - c0, T_arg);      // never past the packed rows or the stated maximum
+        if (c0 < 0) return;
+        nkb = (T + BKW - 1) / BKW;
+        if (pidx >= ((nkb + 1) >> 1)) return;
+        base = ((long)hkv * Ttot + c0) * D;
+        qrow0 = (long)hkv * G * Ttot + c0;
+        qrow_step = Ttot;
+        cbase = (long)hkv * G * nt32 * Ttot + c0;
+        cbase_step = (long)nt32 * Ttot;
+        cstride = Ttot;
+    } else {
+        const long qh0 = G == 1 ? bh : (bh / Hkv) * H + (bh % Hkv) * G;
+        base = bh * (long)T * D;
+        qrow0 = qh0 * (long)T;
+        qrow_step = T;
+        cbase = qh0 * (long)nt32 * T;
+        cbase_step = (long)nt32 * T;
+        cstride = T;
+    }
     const uint16_t* Qg = nullptr;
     const uint16_t* Gg = nullptr;
 
@@ -618,7 +670,7 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     for (int part = 0; part < 2; ++part) {
         const int kb = part == 0 ? pidx : nkb - 1 - pidx;    // small kb = most later queries = first
         if (part == 1 && 2 * pidx == nkb - 1) break;
-        if (SLOW && flags[bh * nkb + kb] == 0) continue;     // only the blocks the fast variant flagged
+        if (SLOW && flags[bh * nkb_arg + kb] == 0) continue; // only the blocks the fast variant flagged
         const int K0 = kb * BKW;
         const int k0 = K0 + wave * 32;                       // this wave's 32 keys
         const int kt32 = k0 >> 5;
@@ -645,11 +697,10 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             for (int r = 0; r < 16; ++r) { dkacc[b][r] = 0.0f; dvacc[b][r] = 0.0f; }
         // the query heads of the group one after the other, into the same accumulators
         for (int g = 0; g < G; ++g) {
-        const long qbh = qh0 + g;
-        Qg = q + qbh * (long)T * D;
-        Gg = dout + qbh * (long)T * D;
-        cag = ca + (qbh * (long)nt32 + kt32) * T;
-        cbg = cb + (qbh * (long)nt32 + kt32) * T;
+        Qg = q + (qrow0 + g * qrow_step) * D;
+        Gg = dout + (qrow0 + g * qrow_step) * D;
+        cag = ca + cbase + g * cbase_step + kt32 * cstride;
+        cbg = cb + cbase + g * cbase_step + kt32 * cstride;
         if (g > 0) barrier_nofence();                        // everyone is done with the stages of the head before
 
         // ---- sweep over 64-row query tiles, from the block's diagonal to the end;
@@ -726,7 +777,7 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         if constexpr (!SLOW) {
             if (__builtin_amdgcn_ballot_w64(dirty) != 0 && lane == 0) atomicOr(&s_dirty, 1);
             __syncthreads();
-            if (tid == 0) flags[bh * nkb + kb] = s_dirty;
+            if (tid == 0) flags[bh * nkb_arg + kb] = s_dirty;
         }
     }
 }
@@ -737,10 +788,11 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 // head, 128-row chunk) partial sums, then one thread per (h, c) adds them in a fixed order.
 constexpr int DR_ROWS = 128;
 
-template <int D>
+template <int D, bool VL>
 __global__ void __launch_bounds__(NTHREADS)
 bwd_drb_partial_kernel(const float* __restrict__ m, const uint16_t* __restrict__ dout,
-                       float* __restrict__ part, int T, int nchunk)
+                       float* __restrict__ part, int T_arg, int nchunk, int H,
+                       const int* __restrict__ cu, int Ttot)
 {
     constexpr int CP = D / 2;                 // column pairs
     constexpr int RG = NTHREADS / CP;         // row groups
@@ -748,11 +800,18 @@ bwd_drb_partial_kernel(const float* __restrict__ m, const uint16_t* __restrict__
     const long bh = blockIdx.y;
     const int chunk = blockIdx.x;
     const int cp = threadIdx.x % CP, rg = threadIdx.x / CP;
+    int T = T_arg;
+    long row0 = bh * (long)T;
+    if constexpr (VL) {                       // bh = sequence * H + head; chunks past the sequence's end give 0
+        const int c0 = cu[bh / H];
+        T = c0 < 0 ? 0 : min(min(cu[bh / H + 1], Ttot) - c0, T_arg);
+        row0 = (bh % H) * (long)Ttot + c0;
+    }
     const int j1 = min(T, (chunk + 1) * DR_ROWS);
     float a0 = 0.0f, a1 = 0.0f;
     for (int j = chunk * DR_ROWS + rg; j < j1; j += RG) {
-        const float w = __expf(m[bh * (long)T + j]);
-        const uint32_t g = *reinterpret_cast<const uint32_t*>(dout + (bh * (long)T + j) * D + 2 * cp);
+        const float w = __expf(m[row0 + j]);
+        const uint32_t g = *reinterpret_cast<const uint32_t*>(dout + (row0 + j) * D + 2 * cp);
         a0 += w * __builtin_bit_cast(float, g << 16);
         a1 += w * __builtin_bit_cast(float, g & 0xffff0000u);
     }
@@ -782,13 +841,15 @@ bwd_drb_sum_kernel(const float* __restrict__ part, float* __restrict__ drb, int 
     drb[h * D + c] = s;
 }
 
-// workspace layout: ca[BH][nt32][T], cb[BH][nt32][T] (fp32), then the per-block flags of
-// the two kernels (int): [BH][nqb], [BH][nkb], then the partial sums of the remainder-bias
-// gradient (fp32): [BH][nchunk][D]
-template <int D>
+// workspace layout: ca[BH][nt32][T], cb[BH][nt32][T] (fp32; [H][nt32][Ttot] for a packed
+// batch), then the per-block flags of the two kernels (int): [BH][nqb], [BH][nkb], then the
+// partial sums of the remainder-bias gradient (fp32): [BH][nchunk][D].  B, T: batch size and
+// length, or for a packed batch (VL) the number of sequences and the longest length.
+template <int D, bool VL>
 hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
                       const float* m, const uint16_t* dout, float* dq, float* dk, float* dv,
-                      float* drb, float* workspace, int B, int H, int Hkv, int T, int passes, hipStream_t stream)
+                      float* drb, float* workspace, int B, int H, int Hkv, int T, int passes, hipStream_t stream,
+                      const int* cu, int Ttot)
 {
     const int BH = B * H;
     const int BHkv = B * Hkv;
@@ -796,35 +857,33 @@ hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, c
     const int nt32 = (T + 31) / 32;
     const int nqb = (T + BQ - 1) / BQ;
     const int nkb = (T + BKW - 1) / BKW;
+    const long ncarry = VL ? (long)H * nt32 * Ttot : (long)BH * nt32 * T;
     float* ca = workspace;
-    float* cb = ca + (long)BH * nt32 * T;
-    int* fq = reinterpret_cast<int*>(cb + (long)BH * nt32 * T);
+    float* cb = ca + ncarry;
+    int* fq = reinterpret_cast<int*>(cb + ncarry);
     int* fk = fq + (long)BH * nqb;
     float* part = reinterpret_cast<float*>(fk + (long)BH * nkb);
     const int nchunk = (T + DR_ROWS - 1) / DR_ROWS;
     const long bq = 8L * ((BH + 7) / 8) * ((nqb + 1) / 2);
     const long bk = 8L * ((BHkv + 7) / 8) * ((nkb + 1) / 2);
     if (bq > 0x7fffffffL || bk > 0x7fffffffL) return hipErrorInvalidValue;
+    if (bq == 0) return hipSuccess;
     hipError_t e = hipSuccess;
+#define SB_DQ(SLOWV, RBV)                                                                                       \
+    hipLaunchKernelGGL((bwd_dq_kernel<D, SLOWV, RBV, VL>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,       \
+                       q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, G, nqb, nt32, cu, Ttot);                 \
+    if ((e = hipGetLastError()) != hipSuccess) return e
+#define SB_DKV(SLOWV, GQAV)                                                                                     \
+    hipLaunchKernelGGL((bwd_dkv_kernel<D, SLOWV, GQAV, VL>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,     \
+                       q, k, v, dout, ca, cb, dk, dv, fk, T, BHkv, H, G, nkb, nt32, cu, Ttot);                  \
+    if ((e = hipGetLastError()) != hipSuccess) return e
     if (passes & 1) {
-        if (rb) {
-            hipLaunchKernelGGL((bwd_dq_kernel<D, false, true>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
-                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, G, nqb, nt32);
-            if ((e = hipGetLastError()) != hipSuccess) return e;
-            hipLaunchKernelGGL((bwd_dq_kernel<D, true, true>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
-                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, G, nqb, nt32);
-        } else {
-            hipLaunchKernelGGL((bwd_dq_kernel<D, false, false>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
-                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, G, nqb, nt32);
-            if ((e = hipGetLastError()) != hipSuccess) return e;
-            hipLaunchKernelGGL((bwd_dq_kernel<D, true, false>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,
-                               q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, G, nqb, nt32);
-        }
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if (rb) { SB_DQ(false, true); SB_DQ(true, true); }
+        else    { SB_DQ(false, false); SB_DQ(true, false); }
         if (drb) {
             if (BH > 65535) return hipErrorInvalidValue;
-            hipLaunchKernelGGL((bwd_drb_partial_kernel<D>), dim3((unsigned)nchunk, (unsigned)BH), dim3(NTHREADS), 0,
-                               stream, m, dout, part, T, nchunk);
+            hipLaunchKernelGGL((bwd_drb_partial_kernel<D, VL>), dim3((unsigned)nchunk, (unsigned)BH), dim3(NTHREADS), 0,
+                               stream, m, dout, part, T, nchunk, H, cu, Ttot);
             if ((e = hipGetLastError()) != hipSuccess) return e;
             hipLaunchKernelGGL((bwd_drb_sum_kernel<D>), dim3((unsigned)H), dim3(D), 0, stream,
                                part, drb, B, H, nchunk);
@@ -832,21 +891,12 @@ hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, c
         }
     }
     if (passes & 2) {
-        if (G > 1) {
-            hipLaunchKernelGGL((bwd_dkv_kernel<D, false, true>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
-                               q, k, v, dout, ca, cb, dk, dv, fk, T, BHkv, H, G, nkb, nt32);
-            if ((e = hipGetLastError()) != hipSuccess) return e;
-            hipLaunchKernelGGL((bwd_dkv_kernel<D, true, true>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
-                               q, k, v, dout, ca, cb, dk, dv, fk, T, BHkv, H, G, nkb, nt32);
-        } else {
-            hipLaunchKernelGGL((bwd_dkv_kernel<D, false, false>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
-                               q, k, v, dout, ca, cb, dk, dv, fk, T, BHkv, H, G, nkb, nt32);
-            if ((e = hipGetLastError()) != hipSuccess) return e;
-            hipLaunchKernelGGL((bwd_dkv_kernel<D, true, false>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,
-                               q, k, v, dout, ca, cb, dk, dv, fk, T, BHkv, H, G, nkb, nt32);
-        }
-        e = hipGetLastError();
+        // a packed batch always takes the grouped variant (a group of one included)
+        if (VL || G > 1) { SB_DKV(false, true); SB_DKV(true, true); }
+        else             { SB_DKV(false, false); SB_DKV(true, false); }
     }
+#undef SB_DQ
+#undef SB_DKV
     return e;
 }
 
@@ -860,14 +910,37 @@ size_t bwd_workspace_bytes(int B, int H, int T, int d)
     return (2 * sizeof(float) * nt32 * T + sizeof(int) * nblk + sizeof(float) * nchunk * d) * (size_t)B * H;
 }
 
+size_t bwd_varlen_workspace_bytes(int nseq, int H, int Ttot, int max_T, int d)
+{
+    const size_t nt32 = (size_t)(max_T + 31) / 32;
+    const size_t nblk = (size_t)(max_T + BQ - 1) / BQ + (size_t)(max_T + BKW - 1) / BKW;
+    const size_t nchunk = (size_t)(max_T + DR_ROWS - 1) / DR_ROWS;
+    return 2 * sizeof(float) * nt32 * (size_t)Ttot * H +
+           (sizeof(int) * nblk + sizeof(float) * nchunk * d) * (size_t)nseq * H;
+}
+
 hipError_t launch_bwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
                            const float* m, const uint16_t* dout, float* dq, float* dk, float* dv,
                            float* drb, float* workspace,
                            int B, int H, int Hkv, int T, int d, int passes, hipStream_t stream)
 {
-    if (d == 32) return launch_one<32>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, B, H, Hkv, T, passes, stream);
-    if (d == 64) return launch_one<64>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, B, H, Hkv, T, passes, stream);
-    return launch_one<128>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, B, H, Hkv, T, passes, stream);
+#define SB_BWD(DD) launch_one<DD, false>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, B, H, Hkv, T, passes, stream, nullptr, 0)
+    if (d == 32) return SB_BWD(32);
+    if (d == 64) return SB_BWD(64);
+    return SB_BWD(128);
+#undef SB_BWD
+}
+
+hipError_t launch_bwd_bf16_varlen(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
+                                  const float* m, const uint16_t* dout, float* dq, float* dk, float* dv,
+                                  float* drb, float* workspace, const int* cu, int nseq, int H, int Hkv,
+                                  int Ttot, int max_T, int d, hipStream_t stream)
+{
+#define SB_BWD(DD) launch_one<DD, true>(q, k, v, rb, m, dout, dq, dk, dv, drb, workspace, nseq, H, Hkv, max_T, 3, stream, cu, Ttot)
+    if (d == 32) return SB_BWD(32);
+    if (d == 64) return SB_BWD(64);
+    return SB_BWD(128);
+#undef SB_BWD
 }
 
 }  // namespace sb

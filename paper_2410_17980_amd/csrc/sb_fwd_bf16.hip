@@ -63,12 +63,17 @@ template <int D> struct FwdCfg {
 
 template <bool B> using bc = std::integral_constant<bool, B>;
 
-template <int D, bool WRITE_M, bool HALT, bool RB>
+// VL: packed variable-length batch.  The tensors are [H][Ttot][D] ([H/G][Ttot][D] for k, v),
+// sequence s occupies rows cu[s] .. cu[s+1]-1, BH counts (sequence, head) pairs and T_arg,
+// nqb_arg describe the longest sequence (they size the grid); a workgroup whose pair of
+// blocks lies beyond its own sequence's end returns at once.
+template <int D, bool WRITE_M, bool HALT, bool RB, bool VL>
 __global__ void __launch_bounds__(64 * NW, 2)
 fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                 const uint16_t* __restrict__ v, const uint16_t* __restrict__ rb,
                 uint16_t* __restrict__ o, float* __restrict__ m,
-                int T, int BH, int H, int G, int nqb, float halt_carry, unsigned long long* __restrict__ tile_counts)
+                int T_arg, int BH, int H, int G, int nqb_arg, float halt_carry,
+                unsigned long long* __restrict__ tile_counts, const int* __restrict__ cu, int Ttot)
 {
     using C = FwdCfg<D>;
     constexpr int NPW = C::NPW;
@@ -80,10 +85,29 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     // the 8 XCDs, so every XCD gets its own heads and K/V of a head stay in one L2.
     const int wg = blockIdx.x;
     const int xcd = wg & 7, slot = wg >> 3;
-    const int npair = (nqb + 1) >> 1;
+    const int npair = (nqb_arg + 1) >> 1;
     const long bh = xcd + 8L * (slot / npair);
     const int pidx = slot % npair;
     if (bh >= BH) return;
+    int T = T_arg, nqb = nqb_arg;
+    long row0, kvrow0;                                  // first row of this head's q / k rows
+    int head;
+    if constexpr (VL) {
+        const int seq = (int)(bh / H);
+        head = (int)(bh % H);
+        const int c0 = cu[seq];
+        T = min(min(cu[seq + 1], Ttot) - c0, T_arg);      // never past the packed rows or the stated maximum
+        if (c0 < 0) return;
+        nqb = (T + BQ - 1) / BQ;
+        if (pidx >= ((nqb + 1) >> 1)) return;
+        row0 = (long)head * Ttot + c0;
+        kvrow0 = (long)(head / G) * Ttot + c0;
+    } else {
+        // grouped kv heads: G consecutive query heads read the same K and V
+        head = (int)(bh % H);
+        row0 = bh * (long)T;
+        kvrow0 = (G == 1 ? bh : (bh / H) * (H / G) + (bh % H) / G) * (long)T;
+    }
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -92,11 +116,9 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int hh = lane >> 5;         // half-wave: keys 16*hh .. 16*hh+15 of a subtile
     const int gg = lane >> 4, li = lane & 15;
 
-    // grouped kv heads: G consecutive query heads read the same K and V
-    const long kvh = G == 1 ? bh : (bh / H) * (H / G) + (bh % H) / G;
-    const uint16_t* Qg = q + bh * (long)T * D;
-    const uint16_t* Kg = k + kvh * (long)T * D;
-    const uint16_t* Vg = v + kvh * (long)T * D;
+    const uint16_t* Qg = q + row0 * D;
+    const uint16_t* Kg = k + kvrow0 * D;
+    const uint16_t* Vg = v + kvrow0 * D;
 
     // ---- per-lane LDS byte offsets inside a 32-row subtile
     int aoff[D / 16];                       // K rows as A operand: row perm_row(n), chunk 2s + hh
@@ -363,7 +385,7 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                 // remainder bias (Appendix C): o_j += (stick left of row j) * r_head.  The
                 // lanes n of both half-waves hold the carry of row q0 + n.
                 const float rem = fast_exp2(-a);
-                const uint16_t* rh = rb + (bh % H) * D;
+                const uint16_t* rh = rb + head * D;
                 float rc[D / 32];
 #pragma unroll
                 for (int b = 0; b < D / 32; ++b)
@@ -375,7 +397,7 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     for (int b = 0; b < D / 32; ++b) oacc[b][r] += rr * rc[b];
                 }
             }
-            uint16_t* Og = o + bh * (long)T * D;
+            uint16_t* Og = o + row0 * D;
             const bool full = q0 + 32 <= T;
 #pragma unroll
             for (int b = 0; b < D / 32; ++b) {
@@ -388,21 +410,23 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     }
                 }
             }
-            if (WRITE_M && hh == 0 && q0 + n < T) m[bh * (long)T + q0 + n] = -a * SB_LN2;
+            if (WRITE_M && hh == 0 && q0 + n < T) m[row0 + q0 + n] = -a * SB_LN2;
         }
     }
 }
 
-template <int D, bool WRITE_M, bool HALT, bool RB>
+template <int D, bool WRITE_M, bool HALT, bool RB, bool VL = false>
 hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
                       uint16_t* o, float* m, int BH, int H, int G, int T, float halt_carry,
-                      unsigned long long* tile_counts, hipStream_t stream)
+                      unsigned long long* tile_counts, hipStream_t stream,
+                      const int* cu = nullptr, int Ttot = 0)
 {
     const int nqb = (T + BQ - 1) / BQ;
     const long blocks = 8L * ((BH + 7) / 8) * ((nqb + 1) / 2);
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((fwd_bf16_kernel<D, WRITE_M, HALT, RB>), dim3((unsigned)blocks), dim3(64 * NW), 0, stream,
-                       q, k, v, rb, o, m, T, BH, H, G, nqb, halt_carry, tile_counts);
+    if (blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL((fwd_bf16_kernel<D, WRITE_M, HALT, RB, VL>), dim3((unsigned)blocks), dim3(64 * NW), 0, stream,
+                       q, k, v, rb, o, m, T, BH, H, G, nqb, halt_carry, tile_counts, cu, Ttot);
     return hipGetLastError();
 }
 
@@ -414,6 +438,27 @@ hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t*
     const int BH = B * H;
     const int G = H / Hkv;
 #define SB_FWD(DD, WM, RBV) launch_one<DD, WM, false, RBV>(q, k, v, rb, o, m, BH, H, G, T, 0.0f, nullptr, stream)
+    if (d == 32) {
+        if (rb) return m ? SB_FWD(32, true, true) : SB_FWD(32, false, true);
+        return m ? SB_FWD(32, true, false) : SB_FWD(32, false, false);
+    }
+    if (d == 64) {
+        if (rb) return m ? SB_FWD(64, true, true) : SB_FWD(64, false, true);
+        return m ? SB_FWD(64, true, false) : SB_FWD(64, false, false);
+    }
+    if (rb) return m ? SB_FWD(128, true, true) : SB_FWD(128, false, true);
+    return m ? SB_FWD(128, true, false) : SB_FWD(128, false, false);
+#undef SB_FWD
+}
+
+hipError_t launch_fwd_bf16_varlen(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
+                                  uint16_t* o, float* m, const int* cu, int nseq, int H, int Hkv,
+                                  int Ttot, int max_T, int d, hipStream_t stream)
+{
+    const int BH = nseq * H;
+    const int G = H / Hkv;
+#define SB_FWD(DD, WM, RBV) \
+    launch_one<DD, WM, false, RBV, true>(q, k, v, rb, o, m, BH, H, G, max_T, 0.0f, nullptr, stream, cu, Ttot)
     if (d == 32) {
         if (rb) return m ? SB_FWD(32, true, true) : SB_FWD(32, false, true);
         return m ? SB_FWD(32, true, false) : SB_FWD(32, false, false);

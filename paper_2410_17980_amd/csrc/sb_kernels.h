@@ -33,6 +33,18 @@ hipError_t launch_bwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t*
                            float* drb, float* workspace,
                            int B, int H, int Hkv, int T, int d, int passes, hipStream_t stream);
 
+// Packed variable-length batches: tensors [H][Ttot][d] ([Hkv][Ttot][d] for k, v, dk, dv), m
+// [H][Ttot]; cu: nseq + 1 ints on the device, cu[0] = 0 <= ... <= cu[nseq] = Ttot; max_T: an
+// upper bound of the longest sequence (sizes the grid and the workspace).
+hipError_t launch_fwd_bf16_varlen(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
+                                  uint16_t* o, float* m, const int* cu, int nseq, int H, int Hkv,
+                                  int Ttot, int max_T, int d, hipStream_t stream);
+size_t bwd_varlen_workspace_bytes(int nseq, int H, int Ttot, int max_T, int d);
+hipError_t launch_bwd_bf16_varlen(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
+                                  const float* m, const uint16_t* dout, float* dq, float* dk, float* dv,
+                                  float* drb, float* workspace, const int* cu, int nseq, int H, int Hkv,
+                                  int Ttot, int max_T, int d, hipStream_t stream);
+
 // MFMA-only diagnostic: operands = at least 1 MiB of bf16 on the device, ticks = 3 x u64 on the device
 hipError_t launch_diag_mfma(const void* operands, int iters, unsigned long long* ticks, hipStream_t stream);
 double diag_mfma_flop(int iters);
