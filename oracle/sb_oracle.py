@@ -195,3 +195,22 @@ def bwd_varlen(q, k, v, dout, cu_seqlens, r=None):
             if r is not None:
                 dr += out[3].reshape(H, d)
     return (dq, dk, dv, dr) if r is not None else (dq, dk, dv)
+
+
+def decode(q, k, v, r=None):
+    """Single-token decode (inference on a key/value cache): q [B,H,d] is the query of the
+    position after the T cached tokens k, v [B,Hkv,T,d], so every cached key is visible.
+    Plain definition: the last row of Eq. 1 on the sequence extended by that position
+    (its own key and value never enter: Eq. 1 is strictly causal).
+    Returns (o [B,H,d], rem [B,H])."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    B, H, d = q.shape
+    _, Hkv, T, _ = k.shape
+    qf = np.zeros((B, H, T + 1, d))
+    qf[:, :, T] = q
+    pad = np.zeros((B, Hkv, 1, d))
+    o, rem = fwd_gqa(qf, np.concatenate([k, pad], axis=2), np.concatenate([v, pad], axis=2),
+                     rows=(T, T + 1), r=r)
+    return o[:, :, 0], rem[:, :, 0]
