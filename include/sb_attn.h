@@ -177,6 +177,24 @@ int sb_attn_varlen_bwd(const void* q, const void* k, const void* v, const void* 
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Single-token decode (inference on a key/value cache; the paper's long-context
+ * evaluation regime): one new query per (batch entry, head) against T cached keys and
+ * values, all visible - the last row of Eq. 1 on the sequence extended by the new position.
+ * q, o: bf16 [B, H, d].  k, v: bf16 [B, Hkv, Tcap, d], rows 0..T-1 valid, 1 <= T <= Tcap
+ * (Tcap = allocated rows per head).  r: optional remainder bias [H, d] bf16 (NULL = none).
+ * m: optional fp32 [B, H], log of the stick left over (NULL = not wanted).
+ * One pass over K and V (bound by HBM bandwidth), split over the keys; partial results are
+ * combined in a fixed order (bit-reproducible).  T <= 524288 (SB_ERR_SHAPE beyond),
+ * B*Hkv <= 65535.  workspace: sb_attn_decode_workspace_bytes(B, H, T, d) bytes of device
+ * scratch, 16-byte aligned (at most 4*B*H*256*(d+1) bytes); SB_ERR_WORKSPACE if NULL or too
+ * small.
+ */
+size_t sb_attn_decode_workspace_bytes(int B, int H, int T, int d);
+int sb_attn_decode(const void* q, const void* k, const void* v, const void* r, void* o, float* m,
+                   void* workspace, size_t workspace_bytes,
+                   int B, int H, int Hkv, int T, int Tcap, int d, void* stream);
+
+/*
  * Measurement aid (not part of the method): runs `iters` x 16 independent
  * 32x32x16 bf16 MFMAs per wavefront, two wavefronts per SIMD on the whole chip,
  * on operands taken from `operands` (device, bf16, at least 1 MiB, 16-byte

@@ -19,6 +19,7 @@ EXPORTS = (
     "sb_attn_bwd_workspace_bytes", "sb_attn_bwd", "sb_attn_bwd_dq", "sb_attn_bwd_dkdv",
     "sb_attn_fwd_rb", "sb_attn_bwd_rb", "sb_attn_fwd_gqa", "sb_attn_bwd_gqa",
     "sb_attn_varlen_fwd", "sb_attn_varlen_bwd_workspace_bytes", "sb_attn_varlen_bwd",
+    "sb_attn_decode_workspace_bytes", "sb_attn_decode",
     "sb_diag_mfma_rate",
     "sb_status_string", "sb_version",
 )
@@ -74,6 +75,10 @@ def load(build_if_missing: bool = True):
     lib.sb_attn_varlen_bwd.argtypes = [vp, vp, vp, vp, fp, vp, fp, fp, fp, fp, vp, ci, ci, ci, ci, ci, ci,
                                        vp, ctypes.c_size_t, vp]
     lib.sb_attn_varlen_bwd.restype = ci
+    lib.sb_attn_decode_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.sb_attn_decode_workspace_bytes.restype = ctypes.c_size_t
+    lib.sb_attn_decode.argtypes = [vp, vp, vp, vp, vp, fp, vp, ctypes.c_size_t, ci, ci, ci, ci, ci, ci, vp]
+    lib.sb_attn_decode.restype = ci
     lib.sb_diag_mfma_rate.argtypes = [vp, ctypes.c_size_t, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.sb_diag_mfma_rate.restype = ci
     lib.sb_status_string.argtypes = [ci]
@@ -336,6 +341,32 @@ def sb_attn_varlen_bwd(q, k, v, m, dout, cu_seqlens, max_T, r=None, dq=None, dk=
                                    nseq, H, Hkv, Ttot, int(max_T), d, ws_ptr, ws_bytes, _stream(stream))
     _check(rc, "sb_attn_varlen_bwd")
     return (dq, dk, dv, dr) if r is not None else (dq, dk, dv)
+
+
+def sb_attn_decode(q, k, v, T=None, r=None, o=None, m=None, want_m=False, workspace=None, stream=None):
+    """Single-token decode: q [B,H,d], cache k, v [B,Hkv,Tcap,d] with the first T rows valid
+    (T defaults to Tcap).  Returns o [B,H,d] (bf16), or (o, m) when m is wanted."""
+    if q.dim() != 3:
+        raise SbAttnError("q: expected [B, H, d]")
+    B, H, d = (int(x) for x in q.shape)
+    _, Hkv, Tcap, _ = _dims(k)
+    T = Tcap if T is None else int(T)
+    if o is None:
+        o = torch.empty_like(q)
+    if m is None and want_m:
+        m = torch.empty((B, H), dtype=torch.float32, device=q.device)
+    need = int(load().sb_attn_decode_workspace_bytes(B, H, T, d))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_ptr = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    kv_shape = (B, Hkv, Tcap, d)
+    rc = load().sb_attn_decode(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, kv_shape, "k"),
+                               _ptr(v, torch.bfloat16, kv_shape, "v"), _ptr(r, torch.bfloat16, (H, d), "r"),
+                               _ptr(o, torch.bfloat16, q.shape, "o"), _ptr(m, torch.float32, (B, H), "m"),
+                               ws_ptr, ws_bytes, B, H, Hkv, T, Tcap, d, _stream(stream))
+    _check(rc, "sb_attn_decode")
+    return (o, m) if m is not None else o
 
 
 def _workspace(workspace, B, H, T, d, device):

@@ -224,6 +224,40 @@ int sb_attn_varlen_bwd(const void* q, const void* k, const void* v, const void* 
     return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
 }
 
+namespace {
+int check_decode(int B, int H, int Hkv, int T, int Tcap, int d)
+{
+    if (B < 1 || H < 1 || Hkv < 1 || H % Hkv != 0 || T < 1 || Tcap < T) return SB_ERR_SHAPE;
+    if (d != 32 && d != 64 && d != 128) return SB_ERR_UNSUPPORTED;
+    if (T > sb::decode_max_T() || (double)B * Hkv > 65535.0 || (double)B * H * (double)Tcap * d >= 1099511627776.0)
+        return SB_ERR_SHAPE;
+    return SB_OK;
+}
+}  // namespace
+
+size_t sb_attn_decode_workspace_bytes(int B, int H, int T, int d)
+{
+    if (check_decode(B, H, H, T, T, d) != SB_OK) return 0;
+    return sb::decode_workspace_bytes(B, H, T, d);
+}
+
+int sb_attn_decode(const void* q, const void* k, const void* v, const void* r, void* o, float* m,
+                   void* workspace, size_t workspace_bytes,
+                   int B, int H, int Hkv, int T, int Tcap, int d, void* stream)
+{
+    if (!q || !k || !v || !o) return SB_ERR_NULL;
+    if (int rc = check_decode(B, H, Hkv, T, Tcap, d)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(r) || !aligned16(o) || !aligned16(m) ||
+        !aligned16(workspace))
+        return SB_ERR_ALIGN;
+    if (!workspace || workspace_bytes < sb::decode_workspace_bytes(B, H, T, d)) return SB_ERR_WORKSPACE;
+    hipError_t e = sb::launch_decode(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                                     static_cast<const uint16_t*>(v), static_cast<const uint16_t*>(r),
+                                     static_cast<uint16_t*>(o), m, static_cast<float*>(workspace),
+                                     B, H, Hkv, T, Tcap, d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
 int sb_diag_mfma_rate(const void* operands, size_t operand_bytes, int iters, unsigned long long* ticks,
                       double* flop, void* stream)
 {

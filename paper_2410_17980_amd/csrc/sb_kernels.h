@@ -45,6 +45,14 @@ hipError_t launch_bwd_bf16_varlen(const uint16_t* q, const uint16_t* k, const ui
                                   float* drb, float* workspace, const int* cu, int nseq, int H, int Hkv,
                                   int Ttot, int max_T, int d, hipStream_t stream);
 
+// Single-token decode: q, o [B][H][d], k, v [B][Hkv][Tcap][d] of which the first T rows are
+// valid, m [B][H] or nullptr, rb [H][d] or nullptr; workspace: decode_workspace_bytes bytes.
+int decode_max_T();
+size_t decode_workspace_bytes(int B, int H, int T, int d);
+hipError_t launch_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
+                         uint16_t* o, float* m, float* workspace,
+                         int B, int H, int Hkv, int T, int Tcap, int d, hipStream_t stream);
+
 // MFMA-only diagnostic: operands = at least 1 MiB of bf16 on the device, ticks = 3 x u64 on the device
 hipError_t launch_diag_mfma(const void* operands, int iters, unsigned long long* ticks, hipStream_t stream);
 double diag_mfma_flop(int iters);
