@@ -15,6 +15,8 @@
 //       softplus, suffix sums over the chunk, weights, weighted sum of the V rows.
 //   decode_combine_kernel  one workgroup per (batch entry, query head): suffix sums of the
 //       a_s over the chunks, O = sum_s 2^-A_s O_s, optional remainder bias, store.
+#include <type_traits>
+
 #include "sb_kernels.h"
 #include "sb_mma.h"
 
@@ -28,6 +30,23 @@ constexpr int DEC_GT = 4;              // query heads of a group handled by one 
 
 __device__ __forceinline__ float bf_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
+
+// sum of v over the aligned group of N lanes (N = 4, 8 or 16) this lane belongs to, in every
+// lane of the group, with data-parallel-primitive adds (no LDS traffic): neighbours inside
+// quads, then the mirrored half row and the mirrored row (all lanes of a quad already hold
+// the same value then, so mirroring reaches the other quads' sum)
+template <int N> __device__ __forceinline__ float group_sum(float v)
+{
+    auto dpp = [](float x, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x),
+                                                                     decltype(ctrl)::value, 0xf, 0xf, false));
+    };
+    v += dpp(v, std::integral_constant<int, 0xB1>{});              // quad_perm [1,0,3,2]
+    v += dpp(v, std::integral_constant<int, 0x4E>{});              // quad_perm [2,3,0,1]
+    if (N >= 8) v += dpp(v, std::integral_constant<int, 0x141>{}); // row_half_mirror
+    if (N >= 16) v += dpp(v, std::integral_constant<int, 0x140>{}); // row_mirror
+    return v;
+}
 
 // sum over the 256 threads' values v of all threads with a HIGHER thread index (exclusive
 // suffix sum), and the total in `total`.  red: 4 floats of LDS; contains a barrier.
@@ -64,7 +83,7 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict
     constexpr int RPI = 64 / LPR;          // rows per wave-wide load
     constexpr int RSTEP = RPI * (DEC_THREADS / 64);
     constexpr int U = 4;                   // rows in flight per lane
-    __shared__ float zs[GT][DEC_CMAX];     // logits (base 2), then weights
+    extern __shared__ float zs[];          // [GT][C]: logits (base 2), then weights
     __shared__ float red[DEC_THREADS / 64];
     __shared__ float ored[DEC_THREADS / 64][GT][D];
 
@@ -109,37 +128,51 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict
                 float s = 0.0f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) s += qf[g][e] * kf[e];
-#pragma unroll
-                for (int off = 1; off < LPR; off <<= 1) s += __shfl_xor(s, off);
-                if (sub == 0 && r0 + u * RSTEP < n) zs[g][r0 + u * RSTEP] = s;
+                s = group_sum<LPR>(s);
+                if (sub == 0 && r0 + u * RSTEP < n) zs[g * C + r0 + u * RSTEP] = s;
             }
         }
     }
     __syncthreads();
 
-    // ---- weights inside the chunk: w[i] = 2^(x_i - sum_{i' >= i} sp2(x_i'))  (Eq. 2)
-    const int E = (C + DEC_THREADS - 1) / DEC_THREADS;         // consecutive keys per thread, <= 8
-#pragma unroll
-    for (int g = 0; g < GT; ++g) {
-        float x[DEC_CMAX / DEC_THREADS], sp[DEC_CMAX / DEC_THREADS];
+    // ---- weights inside the chunk: w[i] = 2^(x_i - sum_{i' >= i} sp2(x_i'))  (Eq. 2).
+    // Two sweeps over consecutive keys per thread: totals, a suffix scan of the totals over
+    // the threads, then the weights (the softplus is evaluated again rather than kept).
+    // With one query head the whole workgroup scans; with GT = 4 each wave takes one head
+    // and no barrier is needed in between.
+    {
+        const int nthr = GT == 1 ? DEC_THREADS : 64;           // threads that share one head's scan
+        const int g = GT == 1 ? 0 : wave;
+        const int t = GT == 1 ? tid : lane;
+        const int E = (C + nthr - 1) / nthr;                   // consecutive keys per thread
+        float* z = zs + g * C;
         float mine = 0.0f;
-#pragma unroll
-        for (int e = 0; e < DEC_CMAX / DEC_THREADS; ++e) {
-            const int i = tid * E + e;
-            const bool ok = e < E && i < n;
-            x[e] = ok ? zs[g][i] : 0.0f;
-            sp[e] = ok ? sp2(x[e]) : 0.0f;
-            mine += sp[e];
+        for (int e = 0; e < E; ++e) {
+            const int i = t * E + e;
+            if (i < n) mine += sp2(z[i]);
         }
-        float total;
-        float run = block_suffix_excl(mine, red, total);       // sp2 of all keys after this thread's
+        float total, run;
+        if constexpr (GT == 1) {
+            run = block_suffix_excl(mine, red, total);         // sp2 of all keys after this thread's
+        } else {
+            float inc = mine;
 #pragma unroll
-        for (int e = DEC_CMAX / DEC_THREADS - 1; e >= 0; --e) {
-            const int i = tid * E + e;
-            run += sp[e];
-            if (e < E && i < n) zs[g][i] = fast_exp2(x[e] - run);
+            for (int off = 1; off < 64; off <<= 1) {
+                const float y = __shfl_down(inc, off);
+                if (lane + off < 64) inc += y;
+            }
+            total = __shfl(inc, 0);
+            run = inc - mine;
         }
-        if (tid == 0 && g0 + g < G) {
+        for (int e = E - 1; e >= 0; --e) {
+            const int i = t * E + e;
+            if (i < n) {
+                const float x = z[i];
+                run += sp2(x);
+                z[i] = fast_exp2(x - run);
+            }
+        }
+        if (t == 0 && g0 + g < G) {
             const long hq = (long)b * H + hkv * G + g0 + g;
             part_a[hq * nchunk + chunk] = total;
         }
@@ -167,7 +200,7 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict
             for (int e = 0; e < 4; ++e) { vf[2 * e] = bf_lo(vw[u][e]); vf[2 * e + 1] = bf_hi(vw[u][e]); }
 #pragma unroll
             for (int g = 0; g < GT; ++g) {
-                const float w = i < n ? zs[g][i] : 0.0f;
+                const float w = i < n ? zs[g * C + i] : 0.0f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc[g][e] += w * vf[e];
             }
@@ -202,7 +235,8 @@ decode_combine_kernel(const float* __restrict__ part_o, const float* __restrict_
                       const uint16_t* __restrict__ rb, uint16_t* __restrict__ o, float* __restrict__ m,
                       int H, int nchunk)
 {
-    constexpr int NG = DEC_THREADS / D;    // groups of threads that split the chunks
+    constexpr int NV = D / 4;              // a thread adds four columns of every NG-th chunk
+    constexpr int NG = DEC_THREADS / NV;
     __shared__ float red[DEC_THREADS / 64];
     __shared__ float ws[DEC_MAXCHUNKS];
     __shared__ float ored[NG][D];
@@ -214,10 +248,16 @@ decode_combine_kernel(const float* __restrict__ part_o, const float* __restrict_
     const float above = block_suffix_excl(a, red, total);
     ws[tid] = fast_exp2(-above);
     __syncthreads();
-    const int c = tid % D, grp = tid / D;
-    float s = 0.0f;
-    for (int ch = grp; ch < nchunk; ch += NG) s += ws[ch] * part_o[(bh * nchunk + ch) * D + c];
-    ored[grp][c] = s;
+    const int c4 = tid % NV, grp = tid / NV;
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    const float4* po = reinterpret_cast<const float4*>(part_o + bh * (long)nchunk * D) + c4;
+#pragma unroll 4
+    for (int ch = grp; ch < nchunk; ch += NG) {
+        const float4 p = po[(long)ch * NV];
+        const float w = ws[ch];
+        s0 += w * p.x; s1 += w * p.y; s2 += w * p.z; s3 += w * p.w;
+    }
+    ored[grp][4 * c4] = s0; ored[grp][4 * c4 + 1] = s1; ored[grp][4 * c4 + 2] = s2; ored[grp][4 * c4 + 3] = s3;
     __syncthreads();
     if (tid < D) {
         float r = 0.0f;
@@ -242,9 +282,9 @@ hipError_t launch_d(const uint16_t* q, const uint16_t* k, const uint16_t* v, con
     const dim3 grid((unsigned)nchunk, (unsigned)(B * Hkv), (unsigned)((G + DEC_GT - 1) / DEC_GT));
     if (G == 1)
         hipLaunchKernelGGL((decode_partial_kernel<D, 1>), dim3((unsigned)nchunk, (unsigned)(B * Hkv), 1u),
-                           dim3(DEC_THREADS), 0, stream, q, k, v, part_o, part_a, T, Tcap, H, G, C, nchunk);
+                           dim3(DEC_THREADS), sizeof(float) * C, stream, q, k, v, part_o, part_a, T, Tcap, H, G, C, nchunk);
     else
-        hipLaunchKernelGGL((decode_partial_kernel<D, DEC_GT>), grid, dim3(DEC_THREADS), 0, stream,
+        hipLaunchKernelGGL((decode_partial_kernel<D, DEC_GT>), grid, dim3(DEC_THREADS), sizeof(float) * DEC_GT * C, stream,
                            q, k, v, part_o, part_a, T, Tcap, H, G, C, nchunk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -254,12 +294,13 @@ hipError_t launch_d(const uint16_t* q, const uint16_t* k, const uint16_t* v, con
 }
 
 // keys per chunk: as few as keep the chunk count within the combine kernel's reach; larger
-// while the launch would still have several thousand workgroups
+// while the launch would still have more than a thousand workgroups (measured: the fixed
+// cost per workgroup outweighs finer balance beyond that)
 int chunk_keys(int BHkv, int T)
 {
     int C = 64;
     while ((T + C - 1) / C > DEC_MAXCHUNKS) C *= 2;
-    while ((long)((T + C - 1) / C) * BHkv > 4096 && C < 1024) C *= 2;
+    while ((long)((T + C - 1) / C) * BHkv > 1024 && C < 1024) C *= 2;
     return C;
 }
 
