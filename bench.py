@@ -107,7 +107,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--cpu-heads", type=int, default=8, help="(b,h) slices the CPU oracle is timed on; 0 = skip")
+    ap.add_argument("--cpu-heads", type=int, default=48, help="(b,h) slices the CPU oracle is timed on; 0 = skip")
     ap.add_argument("--kernel-iters", type=int, default=20, help="launches per kernel for the event timing")
     ap.add_argument("--passes", choices=["fwd", "fwd+bwd"], default=DEFAULT_PASSES,
                     help="what one step runs")
@@ -191,6 +191,29 @@ def main():
     ms_inf = event_time_ms(lambda: sb.sb_attn_fwd(qd, kd, vd, o), args.kernel_iters)
     ms_halt = event_time_ms(lambda: sb.sb_attn_fwd_halt(qd, kd, vd, 1e-9, o), args.kernel_iters)
 
+    # the same on long-range inputs (logits around -6: the stick lasts for hundreds of keys)
+    ql, kl, vl = (t.cuda() for t in inputs.biased_gaussian(B, H, T, d, seed=w.seed, shift=-6.0))
+    counts.zero_()
+    sb.sb_attn_fwd_halt(ql, kl, vl, 1e-9, o, counts)
+    swept_l, full_l = counts.cpu().tolist()
+    ms_inf_l = event_time_ms(lambda: sb.sb_attn_fwd(ql, kl, vl, o), args.kernel_iters)
+    ms_halt_l = event_time_ms(lambda: sb.sb_attn_fwd_halt(ql, kl, vl, 1e-9, o), args.kernel_iters)
+    del ql, kl, vl
+
+    # single-token decode (NOT part of the step or of `value`): one query per head against a
+    # cache of 16384 tokens; bound by HBM bandwidth, K and V are read once
+    Td = 16384
+    gd_ = torch.Generator(device="cpu")
+    gd_.manual_seed(w.seed)
+    kc = torch.randn(B, H, Td, d, generator=gd_, dtype=torch.float32).to(torch.bfloat16).cuda()
+    vc = torch.randn(B, H, Td, d, generator=gd_, dtype=torch.float32).to(torch.bfloat16).cuda()
+    q1 = qd[:, :, 0].contiguous()
+    o1 = torch.empty_like(q1)
+    wsd = torch.empty(sb.load().sb_attn_decode_workspace_bytes(B, H, Td, d), dtype=torch.uint8, device="cuda")
+    ms_dec = event_time_ms(lambda: sb.sb_attn_decode(q1, kc, vc, o=o1, workspace=wsd), 3 * args.kernel_iters)
+    dec_bytes = 2.0 * B * H * Td * d * 2
+    del kc, vc
+
     # the rate the matrix cores sustain on data like the workload's with nothing else running
     mfma_tf, mfma_mhz = sb.sb_diag_mfma_rate(kd.reshape(-1)[: 1 << 21], iters=4000)
 
@@ -225,6 +248,13 @@ def main():
                        "tiles_swept_frac": swept / max(full, 1),
                        "note": "sb_attn_fwd_halt vs sb_attn_fwd (forward without m); depends on the data: "
                                "N(0,1) logits exhaust the stick within a few dozen keys"},
+        "early_halt_long_range": {"eps": 1e-9, "ms_full_sweep": ms_inf_l, "ms_halted": ms_halt_l,
+                                  "speedup": ms_inf_l / ms_halt_l, "tiles_swept_frac": swept_l / max(full_l, 1),
+                                  "inputs": "N(0,1) q, k, v with a bias coordinate: logits about N(-6,1)"},
+        "decode": {"workload": f"B{B} H{H} cache T{Td} d{d}, bf16, one query per head", "ms": ms_dec,
+                   "roofline": {"bound": "hbm", "achieved": dec_bytes / (ms_dec * 1e-3) / 1e9, "peak": 8000.0,
+                                "unit": "GB/s", "frac": dec_bytes / (ms_dec * 1e-3) / 1e9 / 8000.0,
+                                "bytes_per_launch": dec_bytes, "what": "K and V read once"}},
         "mfma_only_ceiling": {"tflops": mfma_tf, "frac_bf16_peak": mfma_tf / PEAK_BF16_TFLOPS,
                               "shader_clock_mhz": mfma_mhz,
                               "what": "32x32x16 bf16 MFMAs alone, operands = the workload's k, 2 waves per SIMD"},
