@@ -126,6 +126,28 @@ def test_workload_4_sampled_heads(sb, oracle, gen):
     assert torch.isfinite(dq).all() and torch.isfinite(dk).all() and torch.isfinite(dv).all()
 
 
+def test_headline_shape_step_sampled_heads(sb, oracle, gen):
+    """The benchmark's step (training forward + backward at B8 H16 T4096 d128, half the heads
+    with k*3, same buffers and launch configuration) on heads the oracle computes one by one,
+    two of them sharp; every gradient finite everywhere."""
+    w = gen.WORKLOADS[2]
+    q, k, v, g = gen.gaussian(w.B, w.H, w.T, w.d, w.seed, w.dtype, w.sharp_half, with_dout=True)
+    qd, kd, vd, gd = dev(q, k, v, g)
+    ws = torch.empty(sb.sb_attn_bwd_workspace_bytes(w.B, w.H, w.T, w.d), dtype=torch.uint8, device="cuda")
+    o, m = sb.sb_attn_fwd_train(qd, kd, vd)
+    dq, dk, dv = sb.sb_attn_bwd(qd, kd, vd, m, gd, workspace=ws)
+    torch.cuda.synchronize()
+    picks = gen.slice_picks(w, 4)
+    assert sum(h >= w.H // 2 for _, h in picks) == 2
+    for b, h in picks:
+        rq, rk, rv = oracle.bwd(to64(q[b, h]), to64(k[b, h]), to64(v[b, h]), to64(g[b, h]))
+        for name, a, r in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+            err = max_abs(to64(a[b, h]), r)
+            print(f"{name}[{b},{h}]: err {err:.3e} max|ref| {np.abs(r).max():.3e}")
+            assert err <= grad_tol(r), f"{name}[{b},{h}]: {err} (max |ref| {np.abs(r).max()})"
+    assert torch.isfinite(dq).all() and torch.isfinite(dk).all() and torch.isfinite(dv).all()
+
+
 def test_bwd_split_passes_equal_the_whole(sb, gen):
     """sb_attn_bwd_dq followed by sb_attn_bwd_dkdv on one workspace is sb_attn_bwd, bit for bit."""
     q, k, v, g = dev(*gen.gaussian(2, 3, 333, 128, seed=21, dtype="bf16", with_dout=True))
