@@ -66,6 +66,33 @@ def test_argument_validation_without_a_gpu(lib):
     assert lib.sb_attn_bwd_rb(p, p, p, None, p, p, p, p, p, p, p, 1 << 20, 1, 1, 8, 64, None) == -1
     assert lib.sb_attn_bwd_rb(p, p, p, p, p, p, p, p, p, None, p, 1 << 20, 1, 1, 8, 64, None) == -1
     assert lib.sb_attn_bwd_rb(p, p, p, p, p, p, p, p, p, p, None, 0, 1, 1, 8, 64, None) == -6
+    # grouped kv heads: H must be a multiple of Hkv
+    assert lib.sb_attn_fwd_gqa(p, p, p, None, p, None, 1, 4, 3, 8, 64, None) == -2
+    assert lib.sb_attn_fwd_gqa(p, p, p, None, p, None, 1, 4, 0, 8, 64, None) == -2
+    assert lib.sb_attn_bwd_gqa(p, p, p, None, p, p, p, p, p, None, p, 1 << 20, 1, 4, 3, 8, 64, None) == -2
+    assert lib.sb_attn_bwd_gqa(p, p, p, p, p, p, p, p, p, None, p, 1 << 20, 1, 4, 2, 8, 64, None) == -1
+    # packed batches: offsets required, 1 <= max_T <= Ttot
+    assert lib.sb_attn_varlen_fwd(p, p, p, None, p, None, None, 2, 2, 2, 100, 60, 64, None) == -1
+    assert lib.sb_attn_varlen_fwd(p, p, p, None, p, None, p, 2, 2, 2, 100, 0, 64, None) == -2
+    assert lib.sb_attn_varlen_fwd(p, p, p, None, p, None, p, 2, 2, 2, 100, 101, 64, None) == -2
+    assert lib.sb_attn_varlen_fwd(p, p, p, None, p, None, p, 0, 2, 2, 100, 60, 64, None) == -2
+    assert lib.sb_attn_varlen_fwd(p, p, p, None, p, None, p, 2, 3, 2, 100, 60, 64, None) == -2
+    assert lib.sb_attn_varlen_fwd(p, p, p, None, p, None, p, 2, 2, 2, 100, 60, 80, None) == -3
+    need_v = lib.sb_attn_varlen_bwd_workspace_bytes(3, 2, 100, 60, 64)
+    assert need_v == 8 * 2 * 100 * 2 + 3 * 2 * (8 + 4 * 64) * 1
+    assert lib.sb_attn_varlen_bwd_workspace_bytes(3, 2, 100, 101, 64) == 0
+    assert lib.sb_attn_varlen_bwd(p, p, p, None, p, p, p, p, p, None, p, 3, 2, 2, 100, 60, 64, p, need_v - 1, None) == -6
+    assert lib.sb_attn_varlen_bwd(p, p, p, None, None, p, p, p, p, None, p, 3, 2, 2, 100, 60, 64, p, need_v, None) == -1
+    # decode: 1 <= T <= Tcap, T within the split's reach
+    need_d = lib.sb_attn_decode_workspace_bytes(2, 4, 1000, 128)
+    assert 0 < need_d <= 4 * 2 * 4 * 256 * 129
+    assert lib.sb_attn_decode_workspace_bytes(2, 4, 0, 128) == 0
+    assert lib.sb_attn_decode(p, p, p, None, p, None, p, need_d, 2, 4, 2, 1000, 999, 128, None) == -2
+    assert lib.sb_attn_decode(p, p, p, None, p, None, p, need_d, 2, 4, 3, 1000, 1000, 128, None) == -2
+    assert lib.sb_attn_decode(p, p, p, None, p, None, p, need_d, 2, 4, 2, 1 << 20, 1 << 20, 128, None) == -2
+    assert lib.sb_attn_decode(p, p, p, None, p, None, None, 0, 2, 4, 2, 1000, 1000, 128, None) == -6
+    assert lib.sb_attn_decode(p, p, p, None, p, None, p, need_d - 1, 2, 4, 2, 1000, 1000, 128, None) == -6
+    assert lib.sb_attn_decode(None, p, p, None, p, None, p, need_d, 2, 4, 2, 1000, 1000, 128, None) == -1
     # workspace: size query, then missing / too small / misaligned workspace
     need = lib.sb_attn_bwd_workspace_bytes(2, 3, 100, 64)
     # two floats per (row, 32-key strip), one int per 128-row query block and key block,
