@@ -254,7 +254,8 @@ def main():
         "decode": {"workload": f"B{B} H{H} cache T{Td} d{d}, bf16, one query per head", "ms": ms_dec,
                    "roofline": {"bound": "hbm", "achieved": dec_bytes / (ms_dec * 1e-3) / 1e9, "peak": 8000.0,
                                 "unit": "GB/s", "frac": dec_bytes / (ms_dec * 1e-3) / 1e9 / 8000.0,
-                                "bytes_per_launch": dec_bytes, "what": "K and V read once"}},
+                                "bytes_per_launch": dec_bytes, "what": "K and V read once",
+                                "traffic": hbm_traffic("decode_partial_kernel")}},
         "mfma_only_ceiling": {"tflops": mfma_tf, "frac_bf16_peak": mfma_tf / PEAK_BF16_TFLOPS,
                               "shader_clock_mhz": mfma_mhz,
                               "what": "32x32x16 bf16 MFMAs alone, operands = the workload's k, 2 waves per SIMD"},
