@@ -59,6 +59,22 @@ def event_time_ms(fn, iters):
     return e0.elapsed_time(e1) / iters
 
 
+def event_times_ms(fn, iters):
+    """Per-launch durations: every launch bracketed by its own pair of events."""
+    import torch
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    ev[-1][1].synchronize()
+    return sorted(a.elapsed_time(b) for a, b in ev)
+
+
+def spread(ts):
+    return {"ms_median": ts[len(ts) // 2], "ms_min": ts[0], "launches": len(ts)}
+
+
 def hbm_traffic(kernel):
     """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see the file)."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic_B8_H16_T4096_d128.txt")
@@ -99,6 +115,7 @@ def cpu_baseline(w, q, k, v, dout, n_heads, with_bwd):
         "sample": f"{n_heads} (b,h) slices of the workload, fwd {t1 - t0:.2f} s + bwd {t2 - t1:.2f} s, float64",
         "fwd_tflops": n_heads * flops_fwd(1, 1, w.T, w.d) / (t1 - t0) / 1e12,
         "bwd_tflops": n_heads * flops_bwd(1, 1, w.T, w.d) / (t2 - t1) / 1e12 if with_bwd else None,
+        "extrapolated_full_workload_s": (t2 - t0) * w.B * w.H / n_heads,
     }
 
 
@@ -108,7 +125,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--cpu-heads", type=int, default=48, help="(b,h) slices the CPU oracle is timed on; 0 = skip")
-    ap.add_argument("--kernel-iters", type=int, default=20, help="launches per kernel for the event timing")
+    ap.add_argument("--kernel-iters", type=int, default=50, help="launches per kernel for the event timing")
     ap.add_argument("--passes", choices=["fwd", "fwd+bwd"], default=DEFAULT_PASSES,
                     help="what one step runs")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -172,10 +189,12 @@ def main():
 
     f_fwd, f_bwd = flops_fwd(B, H, T, d), flops_bwd(B, H, T, d)
     ms_fwd = event_time_ms(fwd, args.kernel_iters)
+    sp_fwd = spread(event_times_ms(fwd, args.kernel_iters))
     tf_fwd = f_fwd / (ms_fwd * 1e-3) / 1e12
     kernels = {"fwd_bf16_kernel": (ms_fwd, f_fwd)}
     if with_bwd:
         ms_bwd = event_time_ms(bwd, args.kernel_iters)
+        sp_bwd = spread(event_times_ms(bwd, args.kernel_iters))
         ms_dq = event_time_ms(lambda: sb.sb_attn_bwd_dq(qd, kd, vd, m, gd, dq, ws), args.kernel_iters)
         ms_dkdv = event_time_ms(lambda: sb.sb_attn_bwd_dkdv(qd, kd, vd, gd, ws, dk, dv), args.kernel_iters)
         tf_bwd = f_bwd / (ms_bwd * 1e-3) / 1e12
@@ -238,9 +257,9 @@ def main():
         "config": {"workload": w.name, "B": B, "H": H, "T": T, "d_head": d,
                    "inputs": "iid N(0,1) bf16, heads h>=H/2 with k*3, seed 2",
                    "step": "fwd_train + bwd" if with_bwd else "fwd_train", "early_halt": "off"},
-        "fwd": {"ms": ms_fwd, "tflops": tf_fwd, "frac_bf16_peak": tf_fwd / PEAK_BF16_TFLOPS},
+        "fwd": {"ms": ms_fwd, "tflops": tf_fwd, "frac_bf16_peak": tf_fwd / PEAK_BF16_TFLOPS, **sp_fwd},
         "bwd": {"ms": ms_bwd, "tflops": tf_bwd, "frac_bf16_peak": tf_bwd / PEAK_BF16_TFLOPS,
-                "dq_pass_ms": ms_dq, "dkdv_pass_ms": ms_dkdv} if with_bwd else None,
+                "dq_pass_ms": ms_dq, "dkdv_pass_ms": ms_dkdv, **sp_bwd} if with_bwd else None,
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": dom_tf, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": dom_tf / PEAK_BF16_TFLOPS, "avg_launch_ms": dom_ms,
                      "flop_per_launch": dom_flop, "traffic": hbm_traffic(dom)},
