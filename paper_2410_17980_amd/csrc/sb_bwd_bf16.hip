@@ -501,7 +501,7 @@ template <int D> struct DkvCfg {
 };
 
 template <int D, bool SLOW, bool GQA, bool VL>
-__global__ void __launch_bounds__(NTHREADS, 1)
+__global__ void __launch_bounds__(NTHREADS, (D == 128 || SLOW) ? 1 : 2)
 bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                const uint16_t* __restrict__ v, const uint16_t* __restrict__ dout,
                const float* __restrict__ ca, const float* __restrict__ cb,
@@ -650,6 +650,14 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     // one 32-query subtile, start to end
     auto subtile = [&](auto mask_c, const char* qtile, float car, float cbl) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_c)::value;
+        if (MASK && n == 0) {
+            // The first query of the diagonal subtile sees none of its keys, and where that
+            // query is the last row of the sequence the query-stationary pass never visits
+            // this subtile: its carries may be unwritten memory.  They multiply zeros, so
+            // any finite value will do.
+            car = 0.0f;
+            cbl = 0.0f;
+        }
         SubtileOut so;
         f32x16 sacc, pacc;
         sp_mfma(qtile, sacc, pacc);

@@ -27,3 +27,9 @@ def check_m(m_gpu: np.ndarray, rem: np.ndarray, rtol=2e-3, atol=2e-3):
     err = np.abs(m_gpu[ok] - ref)
     assert np.all(err <= atol + rtol * np.abs(ref)), float((err - rtol * np.abs(ref)).max())
     assert np.all(m_gpu <= 0.0)
+
+
+def nan_bytes(nbytes: int) -> torch.Tensor:
+    """Device scratch whose every float reads as NaN: a kernel that consumes workspace memory it
+    did not write first shows up as a non-finite result."""
+    return torch.full((max(int(nbytes), 1),), 0xFF, dtype=torch.uint8, device="cuda")

@@ -12,7 +12,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import BF16_TOL, dev, max_abs, to64
+from helpers import BF16_TOL, dev, max_abs, nan_bytes, to64
 
 pytestmark = pytest.mark.gpu
 
@@ -34,7 +34,8 @@ def gen():
 def gpu_grads(sb, q, k, v, g):
     qd, kd, vd, gd = dev(q, k, v, g)
     o, m = sb.sb_attn_fwd_train(qd, kd, vd)
-    dq, dk, dv = sb.sb_attn_bwd(qd, kd, vd, m, gd)
+    ws = nan_bytes(sb.sb_attn_bwd_workspace_bytes(*q.shape))
+    dq, dk, dv = sb.sb_attn_bwd(qd, kd, vd, m, gd, workspace=ws)
     torch.cuda.synchronize()
     return to64(dq), to64(dk), to64(dv)
 
@@ -55,7 +56,7 @@ def check(sb, oracle, q, k, v, g):
     return errs
 
 
-@pytest.mark.parametrize("T", [1, 2, 32, 33, 64, 100, 129, 300])
+@pytest.mark.parametrize("T", [1, 2, 32, 33, 64, 65, 100, 129, 257, 300])
 @pytest.mark.parametrize("d", [32, 64, 128])
 def test_bwd_shapes(sb, oracle, gen, T, d):
     q, k, v, g = gen.gaussian(2, 3, T, d, seed=300 + T + d, dtype="bf16", with_dout=True)

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import BF16_TOL, dev, max_abs, to64
+from helpers import BF16_TOL, dev, max_abs, nan_bytes, to64
 
 pytestmark = pytest.mark.gpu
 
@@ -34,7 +34,9 @@ def make(gen, B, H, Hkv, T, d, seed, kind="gaussian", **kw):
 def check(sb, oracle, q, k, v, T=None, r=None):
     qd, kd, vd = dev(q, k, v)
     rd = r.cuda() if r is not None else None
-    o, m = sb.sb_attn_decode(qd, kd, vd, T=T, r=rd, want_m=True)
+    Tv_ = k.shape[2] if T is None else T
+    ws = nan_bytes(sb.load().sb_attn_decode_workspace_bytes(q.shape[0], q.shape[1], Tv_, q.shape[2]))
+    o, m = sb.sb_attn_decode(qd, kd, vd, T=T, r=rd, want_m=True, workspace=ws)
     torch.cuda.synchronize()
     Tv = k.shape[2] if T is None else T
     ref, rem = oracle.decode(to64(q), to64(k)[:, :, :Tv], to64(v)[:, :, :Tv], r=to64(r) if r is not None else None)

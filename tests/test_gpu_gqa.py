@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import BF16_TOL, check_m, dev, max_abs, to64
+from helpers import BF16_TOL, check_m, dev, max_abs, nan_bytes, to64
 
 pytestmark = pytest.mark.gpu
 
@@ -41,7 +41,7 @@ def check(sb, oracle, q, k, v, g, r=None):
     qd, kd, vd, gd = dev(q, k, v, g)
     rd = r.cuda() if r is not None else None
     o, m = sb.sb_attn_fwd_gqa(qd, kd, vd, r=rd)
-    grads = sb.sb_attn_bwd_gqa(qd, kd, vd, m, gd, r=rd)
+    grads = sb.sb_attn_bwd_gqa(qd, kd, vd, m, gd, r=rd, workspace=nan_bytes(sb.sb_attn_bwd_workspace_bytes(*q.shape)))
     torch.cuda.synchronize()
     r64 = to64(r) if r is not None else None
     ref, rem = oracle.fwd_gqa(to64(q), to64(k), to64(v), r=r64)
@@ -66,7 +66,7 @@ def test_groups(sb, oracle, gen, H, Hkv, T, d):
     check(sb, oracle, *make(gen, 2, H, Hkv, T, d, seed=H * 10 + Hkv))
 
 
-@pytest.mark.parametrize("T", [1, 33, 129])
+@pytest.mark.parametrize("T", [1, 33, 65, 129])
 def test_short_and_ragged(sb, oracle, gen, T):
     check(sb, oracle, *make(gen, 1, 4, 2, T, 128, seed=50 + T))
 

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import BF16_TOL, check_m, dev, max_abs, to64
+from helpers import BF16_TOL, check_m, dev, max_abs, nan_bytes, to64
 
 pytestmark = pytest.mark.gpu
 
@@ -49,7 +49,7 @@ def check_fwd(sb, oracle, q, k, v, r):
 def check_bwd(sb, oracle, q, k, v, r, g):
     qd, kd, vd, rd, m = check_fwd(sb, oracle, q, k, v, r)
     gd, = dev(g)
-    grads = sb.sb_attn_bwd_rb(qd, kd, vd, rd, m, gd)
+    grads = sb.sb_attn_bwd_rb(qd, kd, vd, rd, m, gd, workspace=nan_bytes(sb.sb_attn_bwd_workspace_bytes(*q.shape)))
     torch.cuda.synchronize()
     refs = oracle.bwd(to64(q), to64(k), to64(v), to64(g), r=to64(r))
     for name, a, ref in zip(("dq", "dk", "dv", "dr"), grads, refs):
@@ -61,7 +61,7 @@ def check_bwd(sb, oracle, q, k, v, r, g):
     return grads
 
 
-@pytest.mark.parametrize("T", [1, 2, 33, 64, 129, 300])
+@pytest.mark.parametrize("T", [1, 2, 33, 64, 65, 129, 300])
 @pytest.mark.parametrize("d", [32, 64, 128])
 def test_shapes(sb, oracle, gen, T, d):
     q, k, v, g = gen.gaussian(2, 3, T, d, seed=100 + T + d, with_dout=True)

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import BF16_TOL, check_m, dev, max_abs, to64
+from helpers import BF16_TOL, check_m, dev, max_abs, nan_bytes, to64
 
 pytestmark = pytest.mark.gpu
 
@@ -45,7 +45,8 @@ def check(sb, oracle, q, k, v, g, cu, max_T=None, r=None):
     cud = torch.from_numpy(cu).cuda()
     rd = r.cuda() if r is not None else None
     o, m = sb.sb_attn_varlen_fwd(qd, kd, vd, cud, max_T, r=rd)
-    grads = sb.sb_attn_varlen_bwd(qd, kd, vd, m, gd, cud, max_T, r=rd)
+    ws = nan_bytes(sb.sb_attn_varlen_bwd_workspace_bytes(len(cu) - 1, q.shape[0], q.shape[1], max_T, q.shape[2]))
+    grads = sb.sb_attn_varlen_bwd(qd, kd, vd, m, gd, cud, max_T, r=rd, workspace=ws)
     torch.cuda.synchronize()
     r64 = to64(r) if r is not None else None
     ref, rem = oracle.fwd_varlen(to64(q), to64(k), to64(v), cu, r=r64)
@@ -66,7 +67,7 @@ def check(sb, oracle, q, k, v, g, cu, max_T=None, r=None):
 
 
 @pytest.mark.parametrize("d", [32, 64, 128])
-@pytest.mark.parametrize("lens", [[200], [1, 2, 3], [130, 0, 77, 1, 300], [64, 128, 256], [33, 500, 31]])
+@pytest.mark.parametrize("lens", [[200], [1, 2, 3], [130, 0, 77, 1, 300], [64, 128, 256], [33, 500, 31], [65, 129, 1, 257]])
 def test_length_mixes(sb, oracle, gen, lens, d):
     check(sb, oracle, *packed(gen, 3, 3, lens, d, seed=sum(lens) + d))
 
