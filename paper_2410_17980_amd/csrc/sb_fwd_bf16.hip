@@ -68,7 +68,7 @@ template <bool B> using bc = std::integral_constant<bool, B>;
 // nqb_arg describe the longest sequence (they size the grid); a workgroup whose pair of
 // blocks lies beyond its own sequence's end returns at once.
 template <int D, bool WRITE_M, bool HALT, bool RB, bool VL>
-__global__ void __launch_bounds__(64 * NW, 2)
+__global__ void __launch_bounds__(64 * NW, D == 128 ? 2 : (D == 64 ? 3 : 4))
 fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                 const uint16_t* __restrict__ v, const uint16_t* __restrict__ rb,
                 uint16_t* __restrict__ o, float* __restrict__ m,
