@@ -790,6 +790,322 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     }
 }
 
+// ------------------------------------------------------------------ dK / dV kernel, paired waves
+// The same computation with eight waves per workgroup, two per 32-key strip, for d = 128.
+// There one wave that holds both accumulators (128 registers) and both stationary operands
+// (64) fills a SIMD's register file alone, and a lone wave cannot hide its own latencies.
+// Here the two waves of a strip split the work so that each needs one accumulator only:
+//   - each takes one 32-query subtile of every 64-row tile through S^T, P^T and the
+//     element-wise path ("front") and writes A and dZ (bf16) row-wise into the strip's LDS
+//     scratch;
+//   - after a workgroup barrier, role 0 accumulates dV += A^T dO and role 1 accumulates
+//     dK += dZ^T Q over both subtiles ("back"), reading the transposed operands from the
+//     scratch.
+// No arithmetic is duplicated; the price is a second barrier per tile.  Two waves per SIMD.
+// (Taking turns instead - one wave of a strip in the element-wise part while the other
+// accumulates - was measured too and is much slower: two waves share the vector ALU better
+// than one wave uses it alone.)
+constexpr int NW2 = 8;
+constexpr int NTHREADS2 = 64 * NW2;
+
+template <int D> struct Dkv2Cfg {
+    static constexpr int T_OFF = 2 * StageCfg<D>::STAGE;   // after the double buffer
+    static constexpr int T_SLOT = 32 * TROW;               // one 32x32 bf16 matrix, padded rows
+    static constexpr int T_STRIP = 4 * T_SLOT;             // [subtile][A, dZ]
+    static constexpr int LDS_BYTES = T_OFF + (NW2 / 2) * T_STRIP;
+    static constexpr int LOADS = StageCfg<D>::TILE / 1024; // wave-wide 1 KB loads per matrix of a 64-row tile
+    static constexpr int NPW = (LOADS + NW2 - 1) / NW2;
+};
+
+// workgroup barrier that first waits for this wave's LDS operations (its writes are then
+// visible to the others, its reads have returned)
+__device__ __forceinline__ void barrier_lds()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <int D, bool SLOW, bool GQA, bool VL>
+__global__ void __launch_bounds__(NTHREADS2, 1)
+bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                    const uint16_t* __restrict__ v, const uint16_t* __restrict__ dout,
+                    const float* __restrict__ ca, const float* __restrict__ cb,
+                    float* __restrict__ dk, float* __restrict__ dv, int* __restrict__ flags,
+                    int T_arg, int BH, int H, int G_arg, int nkb_arg, int nt32, const int* __restrict__ cu, int Ttot)
+{
+    using C = StageCfg<D>;
+    using CK = Dkv2Cfg<D>;
+    const int G = GQA ? G_arg : 1;                      // query heads per kv head
+    __shared__ __attribute__((aligned(1024))) char smem[CK::LDS_BYTES];
+    __shared__ int s_dirty;
+
+    const int wg = blockIdx.x;
+    const int xcd = wg & 7, slot = wg >> 3;
+    const int npair = (nkb_arg + 1) >> 1;
+    const long bh = xcd + 8L * (slot / npair);
+    const int pidx = slot % npair;
+    if (bh >= BH) return;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int strip = wave & 3;             // which 32 keys of the block
+    const int role = wave >> 2;             // the subtile of every tile this wave fronts; 0 accumulates dV, 1 dK
+    const int n = lane & 31, hh = lane >> 5;
+    const int gg = lane >> 4, li = lane & 15;
+
+    // bh counts kv heads here (BH = B * H / G of them); its G query heads are qh0 .. qh0+G-1
+    const int Hkv = H / G;
+    int T = T_arg, nkb = nkb_arg;
+    long base;                              // first element of this kv head's K / V / dK / dV rows
+    long qrow0, qrow_step;                  // first Q / dO row of query head qh0, step to the next head
+    long cbase, cbase_step, cstride;        // carries: start for head qh0, step per head, strip stride
+    if constexpr (VL) {
+        const int seq = (int)(bh / Hkv);
+        const int hkv = (int)(bh % Hkv);
+        const int c0 = cu[seq];
+        T = min(min(cu[seq + 1], Ttot) - c0, T_arg);      // never past the packed rows or the stated maximum
+        if (c0 < 0) return;
+        nkb = (T + BKW - 1) / BKW;
+        if (pidx >= ((nkb + 1) >> 1)) return;
+        base = ((long)hkv * Ttot + c0) * D;
+        qrow0 = (long)hkv * G * Ttot + c0;
+        qrow_step = Ttot;
+        cbase = (long)hkv * G * nt32 * Ttot + c0;
+        cbase_step = (long)nt32 * Ttot;
+        cstride = Ttot;
+    } else {
+        const long qh0 = G == 1 ? bh : (bh / Hkv) * H + (bh % Hkv) * G;
+        base = bh * (long)T * D;
+        qrow0 = qh0 * (long)T;
+        qrow_step = T;
+        cbase = qh0 * (long)nt32 * T;
+        cbase_step = (long)nt32 * T;
+        cstride = T;
+    }
+    const uint16_t* Qg = nullptr;
+    const uint16_t* Gg = nullptr;
+
+    // per-lane LDS offsets inside a 32-row Q / dO subtile (natural row order)
+    int boff[D / 16];                       // B-operand reads: row = query n
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) boff[s] = tile_off_nat<D>(n, 2 * s + hh);
+    int qtr[D / 32][2];                     // transposing reads (K-dim = queries)
+    {
+        const int row_l = 8 * (gg >> 1) + (li >> 2);
+        const int cl = 2 * (gg & 1) + ((li & 3) >> 1);
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+                qtr[b][t] = tile_off_nat<D>(row_l + 4 * t, 4 * b + cl) + 8 * (li & 1);
+    }
+    // staging: load i of a matrix (1 KB, rows i*BLK_ROWS ..) goes to wave i % 8
+    int goff[CK::NPW];
+#pragma unroll
+    for (int i = 0; i < CK::NPW; ++i) {
+        const int row = (wave + NW2 * i) * C::BLK_ROWS + lane / C::CPR;
+        goff[i] = (row * D + (((lane % C::CPR) ^ swz_nat<D>(row)) << 3)) * 2;
+    }
+    auto stage = [&](int jt, char* sp) __attribute__((always_inline)) {
+        if ((jt + 1) * TK <= T) {                           // all 64 rows exist
+            const uint16_t* xb = Qg + (long)jt * TK * D;
+            const uint16_t* yb = Gg + (long)jt * TK * D;
+#pragma unroll
+            for (int i = 0; i < CK::NPW; ++i)
+                if (wave + NW2 * i < CK::LOADS) {
+                    dma16_to_lds_saddr(xb, goff[i], sp + (wave + NW2 * i) * 1024);
+                    dma16_to_lds_saddr(yb, goff[i], sp + C::TILE + (wave + NW2 * i) * 1024);
+                }
+        } else {                                            // rows past T are clamped (their results are masked)
+#pragma unroll
+            for (int i = 0; i < CK::NPW; ++i)
+                if (wave + NW2 * i < CK::LOADS) {
+                    const int row = (wave + NW2 * i) * C::BLK_ROWS + lane / C::CPR;
+                    const int c = (lane % C::CPR) ^ swz_nat<D>(row);
+                    const long gr = min(jt * TK + row, T - 1);
+                    dma16_to_lds(Qg + gr * D + c * 8, sp + (wave + NW2 * i) * 1024);
+                    dma16_to_lds(Gg + gr * D + c * 8, sp + C::TILE + (wave + NW2 * i) * 1024);
+                }
+        }
+    };
+    char* const scr = smem + CK::T_OFF + strip * CK::T_STRIP;             // [subtile][A, dZ][32][TROW]
+    const int sw_off = n * TROW + 32 * hh;                                // scratch write: row = query n
+    const int st_off = (8 * (gg >> 1) + (li >> 2)) * TROW + (16 * (gg & 1) + 4 * (li & 3)) * 2;
+
+    const float scale = 1.0f / sqrtf((float)D);
+    const float c2 = SB_LOG2E * scale;
+
+    bf16x8 kf[D / 16], vf[D / 16];          // A operands: the strip's K and V rows (MFMA row n <- key perm_row(n))
+    f32x16 acc[D / 32];                     // dV (role 0) or dK (role 1) of the strip's 32 keys
+    const float* cag = nullptr;
+    const float* cbg = nullptr;
+    bool dirty = false;                     // a chain of this lane left its range (fast variant)
+
+    // this wave's subtile of a tile: logits, dO.v, element-wise path; A and dZ to the scratch
+    auto front = [&](auto mask_c, const char* qtile, float car, float cbl) __attribute__((always_inline)) {
+        constexpr bool MASK = decltype(mask_c)::value;
+        if (MASK && n == 0) {               // sees none of the subtile's keys; its carries may be unwritten
+            car = 0.0f;
+            cbl = 0.0f;
+        }
+        const char* gtile = qtile + C::TILE;
+        u32x4 qw[D / 16], gw[D / 16];
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+            qw[s] = *reinterpret_cast<const u32x4*>(qtile + boff[s]);
+            gw[s] = *reinterpret_cast<const u32x4*>(gtile + boff[s]);
+        }
+        f32x16 sacc, pacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; pacc[r] = 0.0f; }
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], __builtin_bit_cast(bf16x8, qw[s]), sacc, 0, 0, 0);
+            pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s], __builtin_bit_cast(bf16x8, gw[s]), pacc, 0, 0, 0);
+        }
+        SubtileOut so;
+        if constexpr (SLOW) {
+            subtile_math_log<false, MASK>(so, sacc, pacc, car, cbl, c2, n, hh);
+        } else {
+            Chain ch;
+            dirty |= !subtile_stage1<MASK>(ch, sacc, c2, n, hh);
+            subtile_stage2<false, true>(so, ch, pacc, car, cbl, hh);
+        }
+        char* w = scr + role * 2 * CK::T_SLOT + sw_off;
+        *reinterpret_cast<bf16x8*>(w) = so.pa[0];
+        *reinterpret_cast<bf16x8*>(w + 16) = so.pa[1];
+        *reinterpret_cast<bf16x8*>(w + CK::T_SLOT) = so.pz[0];
+        *reinterpret_cast<bf16x8*>(w + CK::T_SLOT + 16) = so.pz[1];
+    };
+    // this wave's accumulator += (A or dZ of subtile u)^T (dO or Q rows of subtile u)
+    auto back = [&](const char* tile, int u) __attribute__((always_inline)) {
+        const char* m = scr + (2 * u + role) * CK::T_SLOT + st_off;
+        const char* x = tile + (role == 0 ? C::TILE : 0) + u * 32 * C::ROW;
+        bf16x8 mt[2], op[D / 16];
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) mt[s2] = tr_pair(m + (16 * s2) * TROW, m + (16 * s2 + 4) * TROW);
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const int ro = (16 * s2) * C::ROW;
+                op[2 * b + s2] = tr_pair(x + ro + qtr[b][0], x + ro + qtr[b][1]);
+            }
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mt[s2], op[2 * b + s2], acc[b], 0, 0, 0);
+    };
+
+    for (int part = 0; part < 2; ++part) {
+        const int kb = part == 0 ? pidx : nkb - 1 - pidx;    // small kb = most later queries = first
+        if (part == 1 && 2 * pidx == nkb - 1) break;
+        if (SLOW && flags[bh * nkb_arg + kb] == 0) continue; // only the blocks the fast variant flagged
+        const int K0 = kb * BKW;
+        const int k0 = K0 + strip * 32;                      // the strip's 32 keys
+        const int kt32 = k0 >> 5;
+        const bool live = k0 < T;
+        if (tid == 0) s_dirty = 0;
+        dirty = false;
+        barrier_lds();                                       // everyone is done with the LDS of the block before
+        {
+            const long kr = min(k0 + perm_row(n), T - 1);
+            const u32x4* ks = reinterpret_cast<const u32x4*>(k + base + kr * D + 8 * hh);
+            const u32x4* vs = reinterpret_cast<const u32x4*>(v + base + kr * D + 8 * hh);
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+                kf[s] = __builtin_bit_cast(bf16x8, ks[2 * s]);
+                vf[s] = __builtin_bit_cast(bf16x8, vs[2 * s]);
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) { asm volatile("" :: "v"(kf[s])); asm volatile("" :: "v"(vf[s])); }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
+
+        // the query heads of the group one after the other, into the same accumulators
+        for (int g = 0; g < G; ++g) {
+        Qg = q + (qrow0 + g * qrow_step) * D;
+        Gg = dout + (qrow0 + g * qrow_step) * D;
+        cag = ca + cbase + g * cbase_step + kt32 * cstride;
+        cbg = cb + cbase + g * cbase_step + kt32 * cstride;
+        if (g > 0) barrier_lds();                            // everyone is done with the LDS of the head before
+
+        // ---- sweep over 64-row query tiles, from the block's diagonal to the end;
+        // iteration it handles tile jt0 + it in buffer it & 1.  The carries of this wave's
+        // subtile are fetched one iteration ahead, and BEFORE the staging loads of that
+        // iteration are issued (vector memory operations complete in order).
+        const int jt0 = K0 / TK;
+        const int ntile = max((T + TK - 1) / TK - jt0, 0);
+        const int ndiag = min(ntile, BKW / TK);              // tiles that touch the diagonal band
+        float cn0 = INFINITY, cn1 = 0.0f;                    // ca, cb of this wave's subtile of the next tile
+        auto load_carries = [&](int jt) __attribute__((always_inline)) {
+            const int j = jt * TK + 32 * role + n;
+            // rows past T: an infinite carry gives A = 0 and G = 0, and with cb = 0 also dZ = 0
+            cn0 = (j < T && live) ? cag[j] : INFINITY;       // a dead strip's rows lie outside the arrays
+            cn1 = (j < T && live) ? cbg[j] : 0.0f;
+        };
+        if (ntile > 0) {
+            load_carries(jt0);
+            stage(jt0, smem);
+        }
+        for (int it = 0; it < ntile; ++it) {
+            dma_wait<0>();
+            barrier_lds();                                   // tile `it` has landed; tile it-1 and its scratch are free
+            const float car = cn0, cbl = cn1;
+            if (it + 1 < ntile) {
+                load_carries(jt0 + it + 1);
+                stage(jt0 + it + 1, smem + ((it + 1) & 1) * C::STAGE);
+            }
+            const char* sp = smem + (it & 1) * C::STAGE;
+            const int jbase = (jt0 + it) * TK;
+            const int j0 = jbase + 32 * role;                // this wave's subtile
+            if (live && j0 < T) {
+                if (it < ndiag) {
+                    if (j0 == k0) front(bc<true>{}, sp + role * 32 * C::ROW, car, cbl);
+                    else if (j0 > k0) front(bc<false>{}, sp + role * 32 * C::ROW, car, cbl);
+                } else {
+                    front(bc<false>{}, sp + role * 32 * C::ROW, car, cbl);
+                }
+            }
+            barrier_lds();                                   // both subtiles' A and dZ are in the scratch
+            if (live) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int ju = jbase + 32 * u;
+                    if (ju >= k0 && ju < T) back(sp, u);
+                }
+            }
+        }
+        }
+
+        // ---- store: acc[b][r] is key row k0 + 8*(r/4) + 4*hh + r%4, column 32b + n
+        if (live) {
+            float* out = (role == 0 ? dv : dk) + base;
+            const float f = role == 0 ? 1.0f : scale;
+#pragma unroll
+            for (int b = 0; b < D / 32; ++b) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = k0 + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    if (key < T) out[(long)key * D + 32 * b + n] = acc[b][r] * f;
+                }
+            }
+        }
+        if constexpr (!SLOW) {
+            if (__builtin_amdgcn_ballot_w64(dirty) != 0 && lane == 0) atomicOr(&s_dirty, 1);
+            __syncthreads();
+            if (tid == 0) flags[bh * nkb_arg + kb] = s_dirty;
+        }
+    }
+}
+
 // ------------------------------------------------------------------ gradient of the remainder bias
 // dr[h][c] = sum over the batch and the rows j of exp(m_j) dO[j][c] (Appendix C: the
 // output holds (stick left of row j) * r_h).  Two deterministic steps: per (batch entry,
@@ -881,9 +1197,16 @@ hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, c
     hipLaunchKernelGGL((bwd_dq_kernel<D, SLOWV, RBV, VL>), dim3((unsigned)bq), dim3(NTHREADS), 0, stream,       \
                        q, k, v, rb, m, dout, dq, ca, cb, fq, T, BH, H, G, nqb, nt32, cu, Ttot);                 \
     if ((e = hipGetLastError()) != hipSuccess) return e
+// d = 128 takes the paired-wave kernel (two waves per SIMD instead of one); smaller head
+// dimensions leave room for two workgroups of the one-wave-per-strip kernel per CU, which
+// is faster there (measured).
 #define SB_DKV(SLOWV, GQAV)                                                                                     \
-    hipLaunchKernelGGL((bwd_dkv_kernel<D, SLOWV, GQAV, VL>), dim3((unsigned)bk), dim3(NTHREADS), 0, stream,     \
-                       q, k, v, dout, ca, cb, dk, dv, fk, T, BHkv, H, G, nkb, nt32, cu, Ttot);                  \
+    if constexpr (D == 128)                                                                                     \
+        hipLaunchKernelGGL((bwd_dkv_pair_kernel<D, SLOWV, GQAV, VL>), dim3((unsigned)bk), dim3(NTHREADS2), 0,   \
+                           stream, q, k, v, dout, ca, cb, dk, dv, fk, T, BHkv, H, G, nkb, nt32, cu, Ttot);      \
+    else                                                                                                        \
+        hipLaunchKernelGGL((bwd_dkv_kernel<D, SLOWV, GQAV, VL>), dim3((unsigned)bk), dim3(NTHREADS), 0,         \
+                           stream, q, k, v, dout, ca, cb, dk, dv, fk, T, BHkv, H, G, nkb, nt32, cu, Ttot);      \
     if ((e = hipGetLastError()) != hipSuccess) return e
     if (passes & 1) {
         if (rb) { SB_DQ(false, true); SB_DQ(true, true); }
