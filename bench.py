@@ -199,7 +199,7 @@ def main():
         ms_dkdv = event_time_ms(lambda: sb.sb_attn_bwd_dkdv(qd, kd, vd, gd, ws, dk, dv), args.kernel_iters)
         tf_bwd = f_bwd / (ms_bwd * 1e-3) / 1e12
         kernels["bwd_dq_kernel"] = (ms_dq, 0.6 * f_bwd)
-        kernels["bwd_dkv_kernel"] = (ms_dkdv, 0.4 * f_bwd)
+        kernels["bwd_dkv_pair_kernel" if d == 128 else "bwd_dkv_kernel"] = (ms_dkdv, 0.4 * f_bwd)
     value = (f_fwd + (f_bwd if with_bwd else 0.0)) / (ms_per_step * 1e-3) / 1e12
 
     # early halt (inference forward; NOT part of the step or of `value`): how much of the sweep
