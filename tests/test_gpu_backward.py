@@ -111,6 +111,24 @@ def test_bwd_twice_agrees_and_overwrites(sb, gen):
     assert not dq1[:, :, 0].any()                                 # first query: no earlier key
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_bwd_is_bit_reproducible_on_a_full_chip(sb, gen, d):
+    """Enough workgroups to fill every CU several times over: a race in the LDS hand-over between
+    the waves of a workgroup would show as run-to-run differences."""
+    B, H, T = 4, 16, 2048
+    q, k, v, g = dev(*gen.gaussian(B, H, T, d, seed=17, dtype="bf16", sharp_half=True, with_dout=True))
+    o, m = sb.sb_attn_fwd_train(q, k, v)
+    ws = nan_bytes(sb.sb_attn_bwd_workspace_bytes(B, H, T, d))
+    ref = [t.clone() for t in sb.sb_attn_bwd(q, k, v, m, g, workspace=ws)]
+    for rep in range(3):
+        ws.fill_(0xFF)
+        out = sb.sb_attn_bwd(q, k, v, m, g, workspace=ws)
+        torch.cuda.synchronize()
+        for name, a, b in zip(("dq", "dk", "dv"), out, ref):
+            assert torch.equal(a, b), f"run {rep}: {name} differs"
+    assert all(torch.isfinite(t).all() for t in ref)
+
+
 def test_workload_4_sampled_heads(sb, oracle, gen):
     w = gen.WORKLOADS[3]
     q, k, v, g = gen.workload_tensors(w)
