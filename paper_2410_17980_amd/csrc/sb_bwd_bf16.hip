@@ -129,7 +129,9 @@ struct Chain {
     float W;         // end of the chain
 };
 
-template <bool MASK>
+// VIA_CHAIN: sigma = e / (1 + e) taken as t_r / W_{r+1} (one add fewer, but serial with the
+// chain): faster in the key-stationary kernel, slower in the query-stationary one (measured)
+template <bool MASK, bool VIA_CHAIN = false>
 __device__ __forceinline__ bool subtile_stage1(Chain& ch, const f32x16& sacc, float c2, int n, int hh)
 {
     float W = 0x1p-60f;
@@ -139,7 +141,7 @@ __device__ __forceinline__ bool subtile_stage1(Chain& ch, const f32x16& sacc, fl
         if (MASK) e = (16 * hh + r < n) ? e : 0.0f;
         ch.t[r] = W * e;
         W += ch.t[r];
-        ch.be[r] = e * __builtin_amdgcn_rcpf(1.0f + e);
+        ch.be[r] = VIA_CHAIN ? ch.t[r] * __builtin_amdgcn_rcpf(W) : e * __builtin_amdgcn_rcpf(1.0f + e);
     }
     ch.W = W;
     return W < 0x1p80f;                                    // false: this lane's chain left its range
@@ -667,7 +669,7 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             subtile_math_log<false, MASK>(so, sacc, pacc, car, cbl, c2, n, hh);
         } else {
             Chain ch;
-            dirty |= !subtile_stage1<MASK>(ch, sacc, c2, n, hh);
+            dirty |= !subtile_stage1<MASK, true>(ch, sacc, c2, n, hh);
             subtile_stage2<false, true>(so, ch, pacc, car, cbl, hh);
         }
         bf16x8 at[2], zt[2];
@@ -970,7 +972,7 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             subtile_math_log<false, MASK>(so, sacc, pacc, car, cbl, c2, n, hh);
         } else {
             Chain ch;
-            dirty |= !subtile_stage1<MASK>(ch, sacc, c2, n, hh);
+            dirty |= !subtile_stage1<MASK, true>(ch, sacc, c2, n, hh);
             subtile_stage2<false, true>(so, ch, pacc, car, cbl, hh);
         }
         char* w = scr + role * 2 * CK::T_SLOT + sw_off;
