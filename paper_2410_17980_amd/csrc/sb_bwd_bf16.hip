@@ -495,6 +495,49 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     }
 }
 
+// Where a kv head's rows and its query heads' rows and carries live (key-stationary kernels).
+// bh counts kv heads (B * H / G of them); its G query heads are qh0 .. qh0+G-1.  Returns
+// false when the workgroup has nothing to do (packed batch: blocks beyond its sequence).
+struct KvHead {
+    int T, nkb;                             // rows and 128-key blocks of this head's sequence
+    long base;                              // first element of the kv head's K / V / dK / dV rows
+    long qrow0, qrow_step;                  // first Q / dO row of query head qh0, step to the next head
+    long cbase, cbase_step, cstride;        // carries: start for head qh0, step per head, strip stride
+};
+
+template <int D, bool VL>
+__device__ __forceinline__ bool kv_head(KvHead& kh, long bh, int pidx, int T_arg, int nkb_arg, int H, int G,
+                                        int nt32, const int* __restrict__ cu, int Ttot)
+{
+    const int Hkv = H / G;
+    if constexpr (VL) {
+        const int seq = (int)(bh / Hkv);
+        const int hkv = (int)(bh % Hkv);
+        const int c0 = cu[seq];
+        kh.T = min(min(cu[seq + 1], Ttot) - c0, T_arg);   // never past the packed rows or the stated maximum
+        if (c0 < 0) return false;
+        kh.nkb = (kh.T + BKW - 1) / BKW;
+        if (pidx >= ((kh.nkb + 1) >> 1)) return false;
+        kh.base = ((long)hkv * Ttot + c0) * D;
+        kh.qrow0 = (long)hkv * G * Ttot + c0;
+        kh.qrow_step = Ttot;
+        kh.cbase = (long)hkv * G * nt32 * Ttot + c0;
+        kh.cbase_step = (long)nt32 * Ttot;
+        kh.cstride = Ttot;
+    } else {
+        const long qh0 = G == 1 ? bh : (bh / Hkv) * H + (bh % Hkv) * G;
+        kh.T = T_arg;
+        kh.nkb = nkb_arg;
+        kh.base = bh * (long)T_arg * D;
+        kh.qrow0 = qh0 * (long)T_arg;
+        kh.qrow_step = T_arg;
+        kh.cbase = qh0 * (long)nt32 * T_arg;
+        kh.cbase_step = (long)nt32 * T_arg;
+        kh.cstride = T_arg;
+    }
+    return true;
+}
+
 // ------------------------------------------------------------------ dK / dV kernel
 template <int D> struct DkvCfg {
     static constexpr int T_OFF = 2 * StageCfg<D>::STAGE;   // after the double buffer
@@ -529,35 +572,12 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int n = lane & 31, hh = lane >> 5;
     const int gg = lane >> 4, li = lane & 15;
 
-    // bh counts kv heads here (BH = B * H / G of them); its G query heads are qh0 .. qh0+G-1
-    const int Hkv = H / G;
-    int T = T_arg, nkb = nkb_arg;
-    long base;                              // first element of this kv head's K / V / dK / dV rows
-    long qrow0, qrow_step;                  // first Q / dO row of query head qh0, step to the next head
-    long cbase, cbase_step, cstride;        // carries: start for head qh0, step per head, strip stride
-    if constexpr (VL) {
-        const int seq = (int)(bh / Hkv);
-        const int hkv = (int)(bh % Hkv);
-        const int c0 = cu[seq];
-        T = min(min(cu[seq + 1], Ttot) - c0, T_arg);      // never past the packed rows or the stated maximum
-        if (c0 < 0) return;
-        nkb = (T + BKW - 1) / BKW;
-        if (pidx >= ((nkb + 1) >> 1)) return;
-        base = ((long)hkv * Ttot + c0) * D;
-        qrow0 = (long)hkv * G * Ttot + c0;
-        qrow_step = Ttot;
-        cbase = (long)hkv * G * nt32 * Ttot + c0;
-        cbase_step = (long)nt32 * Ttot;
-        cstride = Ttot;
-    } else {
-        const long qh0 = G == 1 ? bh : (bh / Hkv) * H + (bh % Hkv) * G;
-        base = bh * (long)T * D;
-        qrow0 = qh0 * (long)T;
-        qrow_step = T;
-        cbase = qh0 * (long)nt32 * T;
-        cbase_step = (long)nt32 * T;
-        cstride = T;
-    }
+    // bh counts kv heads here (BH = B * H / G of them)
+    KvHead kh;
+    if (!kv_head<D, VL>(kh, bh, pidx, T_arg, nkb_arg, H, G, nt32, cu, Ttot)) return;
+    const int T = kh.T, nkb = kh.nkb;
+    const long base = kh.base, qrow0 = kh.qrow0, qrow_step = kh.qrow_step;
+    const long cbase = kh.cbase, cbase_step = kh.cbase_step, cstride = kh.cstride;
     const uint16_t* Qg = nullptr;
     const uint16_t* Gg = nullptr;
 
@@ -857,35 +877,12 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     const int n = lane & 31, hh = lane >> 5;
     const int gg = lane >> 4, li = lane & 15;
 
-    // bh counts kv heads here (BH = B * H / G of them); its G query heads are qh0 .. qh0+G-1
-    const int Hkv = H / G;
-    int T = T_arg, nkb = nkb_arg;
-    long base;                              // first element of this kv head's K / V / dK / dV rows
-    long qrow0, qrow_step;                  // first Q / dO row of query head qh0, step to the next head
-    long cbase, cbase_step, cstride;        // carries: start for head qh0, step per head, strip stride
-    if constexpr (VL) {
-        const int seq = (int)(bh / Hkv);
-        const int hkv = (int)(bh % Hkv);
-        const int c0 = cu[seq];
-        T = min(min(cu[seq + 1], Ttot) - c0, T_arg);      // never past the packed rows or the stated maximum
-        if (c0 < 0) return;
-        nkb = (T + BKW - 1) / BKW;
-        if (pidx >= ((nkb + 1) >> 1)) return;
-        base = ((long)hkv * Ttot + c0) * D;
-        qrow0 = (long)hkv * G * Ttot + c0;
-        qrow_step = Ttot;
-        cbase = (long)hkv * G * nt32 * Ttot + c0;
-        cbase_step = (long)nt32 * Ttot;
-        cstride = Ttot;
-    } else {
-        const long qh0 = G == 1 ? bh : (bh / Hkv) * H + (bh % Hkv) * G;
-        base = bh * (long)T * D;
-        qrow0 = qh0 * (long)T;
-        qrow_step = T;
-        cbase = qh0 * (long)nt32 * T;
-        cbase_step = (long)nt32 * T;
-        cstride = T;
-    }
+    // bh counts kv heads here (BH = B * H / G of them)
+    KvHead kh;
+    if (!kv_head<D, VL>(kh, bh, pidx, T_arg, nkb_arg, H, G, nt32, cu, Ttot)) return;
+    const int T = kh.T, nkb = kh.nkb;
+    const long base = kh.base, qrow0 = kh.qrow0, qrow_step = kh.qrow_step;
+    const long cbase = kh.cbase, cbase_step = kh.cbase_step, cstride = kh.cstride;
     const uint16_t* Qg = nullptr;
     const uint16_t* Gg = nullptr;
 
