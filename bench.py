@@ -279,6 +279,11 @@ def main():
                               "shader_clock_mhz": mfma_mhz,
                               "what": "32x32x16 bf16 MFMAs alone, operands = the workload's k, 2 waves per SIMD"},
     }
+    # the same rates against what the matrix cores sustain on this data (measured above)
+    out["fwd"]["frac_mfma_only_ceiling"] = tf_fwd / mfma_tf
+    if with_bwd:
+        out["bwd"]["frac_mfma_only_ceiling"] = tf_bwd / mfma_tf
+    out["roofline"]["frac_mfma_only_ceiling"] = dom_tf / mfma_tf
     if args.cpu_heads > 0:
         out["cpu_baseline"] = cpu_baseline(w, q, k, v, dout, args.cpu_heads, with_bwd)
     print(json.dumps(out))
