@@ -167,6 +167,24 @@ def test_headline_shape_step_sampled_heads(sb, oracle, gen):
     assert torch.isfinite(dq).all() and torch.isfinite(dk).all() and torch.isfinite(dv).all()
 
 
+def test_long_context_backward_one_head(sb, oracle, gen):
+    """T = 8192: many tiles per block and 64 blocks per head; one (b, h) slice against the oracle
+    (which needs 16 T^2 bytes = 1 GiB of host scratch for it)."""
+    B, H, T, d = 1, 8, 8192, 128
+    q, k, v, g = gen.gaussian(B, H, T, d, seed=23, dtype="bf16", sharp_half=True, with_dout=True)
+    qd, kd, vd, gd = dev(q, k, v, g)
+    o, m = sb.sb_attn_fwd_train(qd, kd, vd)
+    dq, dk, dv = sb.sb_attn_bwd(qd, kd, vd, m, gd, workspace=nan_bytes(sb.sb_attn_bwd_workspace_bytes(B, H, T, d)))
+    torch.cuda.synchronize()
+    assert torch.isfinite(dq).all() and torch.isfinite(dk).all() and torch.isfinite(dv).all()
+    for h in (1, 6):                                   # a plain and a sharp head
+        rq, rk, rv = oracle.bwd(to64(q[0, h]), to64(k[0, h]), to64(v[0, h]), to64(g[0, h]))
+        for name, a, r in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+            err = max_abs(to64(a[0, h]), r)
+            print(f"{name}[0,{h}]: err {err:.3e} max|ref| {np.abs(r).max():.3e}")
+            assert err <= grad_tol(r), f"{name}[0,{h}]: {err} (max |ref| {np.abs(r).max()})"
+
+
 def test_bwd_split_passes_equal_the_whole(sb, gen):
     """sb_attn_bwd_dq followed by sb_attn_bwd_dkdv on one workspace is sb_attn_bwd, bit for bit."""
     q, k, v, g = dev(*gen.gaussian(2, 3, 333, 128, seed=21, dtype="bf16", with_dout=True))
