@@ -105,6 +105,21 @@ def test_long_cache(sb, oracle, gen):
     check(sb, oracle, *make(gen, 1, 4, 2, 70000, 128, seed=11), r=gen.remainder_embedding(4, 128, seed=12))
 
 
+def test_largest_cache_the_split_reaches(sb, oracle, gen):
+    """T = 524288 = 256 chunks of 2048 keys, the most one call takes."""
+    T, d = 524288, 64
+    q, _, _ = gen.biased_gaussian(1, 1, 1, d, seed=21, shift=-8.0)
+    _, k, v = gen.biased_gaussian(1, 1, T, d, seed=22, shift=-8.0)
+    q = q[:, :, 0].contiguous()
+    o, m = sb.sb_attn_decode(*dev(q, k, v), want_m=True)
+    torch.cuda.synchronize()
+    ref, rem = oracle.decode(to64(q), to64(k), to64(v))
+    assert max_abs(to64(o), ref) <= BF16_TOL
+    assert np.allclose(to64(m), np.log(rem), rtol=2e-3, atol=2e-3)
+    with pytest.raises(sb.SbAttnError):
+        sb.sb_attn_decode(*dev(q, k, v), T=T, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+
+
 def test_argument_errors(sb, gen):
     q, k, v = make(gen, 1, 4, 3, 40, 64, seed=13)
     with pytest.raises(sb.SbAttnError):

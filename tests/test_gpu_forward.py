@@ -181,6 +181,20 @@ def test_workload_5_long_context_tail_rows(sb, oracle, gen):
 
 
 # ---------------------------------------------------------------- early halt (inference forward)
+def test_very_long_sequence_sampled_rows(sb, oracle, gen):
+    """T = 65536 (1024 key tiles per row block, 64-bit row offsets in play): rows the oracle computes
+    one by one, at the start, in the middle and at the end, on long-range inputs so that the carry
+    matters across thousands of keys."""
+    T, d = 65536, 64
+    q, k, v = gen.biased_gaussian(1, 2, T, d, seed=31, shift=-6.0, dtype="bf16")
+    o, m = sb.sb_attn_fwd_train(*dev(q, k, v))
+    torch.cuda.synchronize()
+    for r0 in (0, 32760, T - 64):
+        ref, rem = oracle.fwd(to64(q), to64(k), to64(v), rows=(r0, r0 + 64))
+        assert max_abs(to64(o[:, :, r0:r0 + 64]), ref) <= BF16_TOL
+        check_m(to64(m[:, :, r0:r0 + 64]), rem)
+
+
 def test_halt_matches_oracle_and_skips_tiles(sb, oracle, gen):
     """N(0,1) logits use up the stick within a few dozen keys: almost every tile beyond the
     diagonal band is skipped, and the output still matches the oracle."""
