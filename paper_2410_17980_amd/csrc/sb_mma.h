@@ -90,6 +90,14 @@ __device__ __forceinline__ void both_halves(float v, float& lo, float& hi)
     hi = __builtin_bit_cast(float, (int)sw[1]);
 }
 
+// LDS byte address of a pointer into a __shared__ array.  A generic pointer to LDS is the LDS
+// address in its low half and the aperture in its high half, so this is a truncation; the
+// address-space cast would add a null check (compare + select) per use.
+__device__ __forceinline__ uint32_t lds_offset(const char* p)
+{
+    return (uint32_t)(uintptr_t)p;
+}
+
 // Direct global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): lane l
 // of the wave writes LDS bytes [lds_base + 16 l, +16) with the 16 bytes at its own
 // global address; lds_base must be wave-uniform.  Issued through inline assembly so
@@ -98,7 +106,7 @@ __device__ __forceinline__ void both_halves(float v, float& lo, float& hi)
 // Completion is counted in vmcnt, in issue order.
 __device__ __forceinline__ void dma16_to_lds(const void* gptr, const char* lds_base)
 {
-    const uint32_t lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)SB_LDS(const char, lds_base));
+    const uint32_t lds = __builtin_amdgcn_readfirstlane(lds_offset(lds_base));
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                  :: "s"(lds), "v"(gptr) : "memory");
 }
@@ -106,7 +114,7 @@ __device__ __forceinline__ void dma16_to_lds(const void* gptr, const char* lds_b
 // same, with the global address given as a wave-uniform base plus a per-lane byte offset
 __device__ __forceinline__ void dma16_to_lds_saddr(const void* gbase, int lane_off, const char* lds_base)
 {
-    const uint32_t lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)SB_LDS(const char, lds_base));
+    const uint32_t lds = __builtin_amdgcn_readfirstlane(lds_offset(lds_base));
     const uint64_t b = (uint64_t)(uintptr_t)gbase;
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
     const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
