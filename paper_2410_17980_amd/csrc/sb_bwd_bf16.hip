@@ -839,15 +839,6 @@ template <int D> struct Dkv2Cfg {
     static constexpr int NPW = (LOADS + NW2 - 1) / NW2;
 };
 
-// workgroup barrier that first waits for this wave's LDS operations (its writes are then
-// visible to the others, its reads have returned)
-__device__ __forceinline__ void barrier_lds()
-{
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
 template <int D, bool SLOW, bool GQA, bool VL>
 __global__ void __launch_bounds__(NTHREADS2, 1)
 bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
@@ -1120,8 +1111,8 @@ bwd_drb_partial_kernel(const float* __restrict__ m, const uint16_t* __restrict__
     constexpr int CP = D / 2;                 // column pairs
     constexpr int RG = NTHREADS / CP;         // row groups
     __shared__ float red[RG][D];
-    const long bh = blockIdx.y;
-    const int chunk = blockIdx.x;
+    const long bh = blockIdx.x / nchunk;      // one grid dimension: no 65535 limit on the heads
+    const int chunk = blockIdx.x % nchunk;
     const int cp = threadIdx.x % CP, rg = threadIdx.x / CP;
     int T = T_arg;
     long row0 = bh * (long)T;
@@ -1189,7 +1180,8 @@ hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, c
     const int nchunk = (T + DR_ROWS - 1) / DR_ROWS;
     const long bq = 8L * ((BH + 7) / 8) * ((nqb + 1) / 2);
     const long bk = 8L * ((BHkv + 7) / 8) * ((nkb + 1) / 2);
-    if (bq > 0x7fffffffL || bk > 0x7fffffffL) return hipErrorInvalidValue;
+    // checked before the first launch, so that an error leaves nothing enqueued
+    if (bq > 0x7fffffffL || bk > 0x7fffffffL || nchunk * (long)BH > 0x7fffffffL) return hipErrorInvalidValue;
     if (bq == 0) return hipSuccess;
     hipError_t e = hipSuccess;
 #define SB_DQ(SLOWV, RBV)                                                                                       \
@@ -1211,8 +1203,7 @@ hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, c
         if (rb) { SB_DQ(false, true); SB_DQ(true, true); }
         else    { SB_DQ(false, false); SB_DQ(true, false); }
         if (drb) {
-            if (BH > 65535) return hipErrorInvalidValue;
-            hipLaunchKernelGGL((bwd_drb_partial_kernel<D, VL>), dim3((unsigned)nchunk, (unsigned)BH), dim3(NTHREADS), 0,
+            hipLaunchKernelGGL((bwd_drb_partial_kernel<D, VL>), dim3((unsigned)(nchunk * (long)BH)), dim3(NTHREADS), 0,
                                stream, m, dout, part, T, nchunk, H, cu, Ttot);
             if ((e = hipGetLastError()) != hipSuccess) return e;
             hipLaunchKernelGGL((bwd_drb_sum_kernel<D>), dim3((unsigned)H), dim3(D), 0, stream,

@@ -336,7 +336,10 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         stage_tile(max(ntile - 1, 0), 0);
         auto begin_iter = [&](int it) __attribute__((always_inline)) {
             dma_wait<0>();                                   // this wave's share of tile `it` has landed
-            barrier_nofence();                               // ... everyone's has, and tile it-1 is no longer read
+            // ... everyone's has, and tile it-1 is no longer read.  The halting variant also
+            // publishes its flags through LDS here: their writes must have completed first,
+            // or the waves of a workgroup could disagree about leaving the loop.
+            if constexpr (HALT) barrier_lds(); else barrier_nofence();
             stage_tile(max(ntile - 2 - it, 0), (it + 1) % NS);
             return (const char*)(smem + (it % NS) * C::STAGE);
         };

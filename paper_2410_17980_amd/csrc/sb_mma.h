@@ -103,12 +103,15 @@ __device__ __forceinline__ uint32_t lds_offset(const char* p)
 // global address; lds_base must be wave-uniform.  Issued through inline assembly so
 // that the compiler's wait-count pass does not see an LDS write it would guard
 // every later LDS read against; the caller orders it with dma_wait<N>() + barrier.
-// Completion is counted in vmcnt, in issue order.
+// Completion is counted in vmcnt, in issue order.  The LDS base travels in M0, which
+// is handed over as a register operand: the compiler writes it and knows it is in use
+// (the s_nop covers the wait state between a scalar write of M0 and this instruction,
+// which the compiler cannot see into).
 __device__ __forceinline__ void dma16_to_lds(const void* gptr, const char* lds_base)
 {
     const uint32_t lds = __builtin_amdgcn_readfirstlane(lds_offset(lds_base));
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(lds), "v"(gptr) : "memory");
+    asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "{m0}"(lds), "v"(gptr) : "memory");
 }
 
 // same, with the global address given as a wave-uniform base plus a per-lane byte offset
@@ -119,8 +122,8 @@ __device__ __forceinline__ void dma16_to_lds_saddr(const void* gbase, int lane_o
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
     const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
     const uint64_t sb = ((uint64_t)hi << 32) | lo;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds), "v"(lane_off), "s"(sb) : "memory");
+    asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "{m0}"(lds), "v"(lane_off), "s"(sb) : "memory");
 }
 
 // wait until at most N of this wave's vector-memory operations are outstanding
@@ -134,6 +137,15 @@ template <int N> __device__ __forceinline__ void dma_wait()
 __device__ __forceinline__ void barrier_nofence()
 {
     asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// workgroup barrier that first waits for this wave's LDS operations (its writes are then
+// visible to the others, its reads have returned)
+__device__ __forceinline__ void barrier_lds()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 }
