@@ -195,6 +195,25 @@ int sb_attn_decode(const void* q, const void* k, const void* v, const void* r, v
                    int B, int H, int Hkv, int T, int Tcap, int d, void* stream);
 
 /*
+ * sb_attn_decode for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and kernels as sb_attn_decode, minus the workspace: the partial results
+ * of the key chunks go to a scratch array of SB_DECODE_STATIC_BYTES that is part of the
+ * library's device image (every GPU the library runs on holds its own copy until the process
+ * ends).  The call allocates and frees nothing; the first call on a device looks up the
+ * array's device address (hipGetSymbolAddress) and keeps it.
+ * Limit: sb_attn_decode_workspace_bytes(B, H, T, d) <= SB_DECODE_STATIC_BYTES, otherwise
+ * SB_ERR_WORKSPACE and nothing is enqueued (B*H*min(ceil(T/64), 256)*(d+1)*4 bytes: e.g.
+ * B*H = 128 heads of d = 128 at any T, or 256 heads up to T = 8192).
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU
+ * (different streams, or different host threads) race on it.  Calls on one stream are safe
+ * back to back; every element a call reads it has written itself, so nothing needs clearing.
+ */
+#define SB_DECODE_STATIC_BYTES ((size_t)33554432)
+int sb_attn_decode_static(const void* q, const void* k, const void* v, const void* r, void* o, float* m,
+                          int B, int H, int Hkv, int T, int Tcap, int d, void* stream);
+
+/*
  * Measurement aid (not part of the method): runs `iters` x 16 independent
  * 32x32x16 bf16 MFMAs per wavefront, two wavefronts per SIMD on the whole chip,
  * on operands taken from `operands` (device, bf16, at least 1 MiB, 16-byte

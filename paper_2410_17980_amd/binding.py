@@ -19,7 +19,7 @@ EXPORTS = (
     "sb_attn_bwd_workspace_bytes", "sb_attn_bwd", "sb_attn_bwd_dq", "sb_attn_bwd_dkdv",
     "sb_attn_fwd_rb", "sb_attn_bwd_rb", "sb_attn_fwd_gqa", "sb_attn_bwd_gqa",
     "sb_attn_varlen_fwd", "sb_attn_varlen_bwd_workspace_bytes", "sb_attn_varlen_bwd",
-    "sb_attn_decode_workspace_bytes", "sb_attn_decode",
+    "sb_attn_decode_workspace_bytes", "sb_attn_decode", "sb_attn_decode_static",
     "sb_diag_mfma_rate",
     "sb_status_string", "sb_version",
 )
@@ -79,6 +79,8 @@ def load(build_if_missing: bool = True):
     lib.sb_attn_decode_workspace_bytes.restype = ctypes.c_size_t
     lib.sb_attn_decode.argtypes = [vp, vp, vp, vp, vp, fp, vp, ctypes.c_size_t, ci, ci, ci, ci, ci, ci, vp]
     lib.sb_attn_decode.restype = ci
+    lib.sb_attn_decode_static.argtypes = [vp, vp, vp, vp, vp, fp, ci, ci, ci, ci, ci, ci, vp]
+    lib.sb_attn_decode_static.restype = ci
     lib.sb_diag_mfma_rate.argtypes = [vp, ctypes.c_size_t, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.sb_diag_mfma_rate.restype = ci
     lib.sb_status_string.argtypes = [ci]
@@ -366,6 +368,23 @@ def sb_attn_decode(q, k, v, T=None, r=None, o=None, m=None, want_m=False, worksp
                                _ptr(o, torch.bfloat16, q.shape, "o"), _ptr(m, torch.float32, (B, H), "m"),
                                ws_ptr, ws_bytes, B, H, Hkv, T, Tcap, d, _stream(stream))
     _check(rc, "sb_attn_decode")
+    return (o, m) if m is not None else o
+
+
+def sb_attn_decode_static(q, k, v, o, T=None, r=None, m=None, stream=None):
+    """sb_attn_decode on the library's own static device scratch: nothing is allocated, so the
+    caller passes every output (o [B,H,d] bf16, optionally m [B,H] fp32)."""
+    if q.dim() != 3:
+        raise SbAttnError("q: expected [B, H, d]")
+    B, H, d = (int(x) for x in q.shape)
+    _, Hkv, Tcap, _ = _dims(k)
+    T = Tcap if T is None else int(T)
+    kv_shape = (B, Hkv, Tcap, d)
+    rc = load().sb_attn_decode_static(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, kv_shape, "k"),
+                                      _ptr(v, torch.bfloat16, kv_shape, "v"), _ptr(r, torch.bfloat16, (H, d), "r"),
+                                      _ptr(o, torch.bfloat16, q.shape, "o"), _ptr(m, torch.float32, (B, H), "m"),
+                                      B, H, Hkv, T, Tcap, d, _stream(stream))
+    _check(rc, "sb_attn_decode_static")
     return (o, m) if m is not None else o
 
 

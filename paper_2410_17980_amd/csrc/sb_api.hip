@@ -258,6 +258,23 @@ int sb_attn_decode(const void* q, const void* k, const void* v, const void* r, v
     return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
 }
 
+int sb_attn_decode_static(const void* q, const void* k, const void* v, const void* r, void* o, float* m,
+                          int B, int H, int Hkv, int T, int Tcap, int d, void* stream)
+{
+    if (!q || !k || !v || !o) return SB_ERR_NULL;
+    if (int rc = check_decode(B, H, Hkv, T, Tcap, d)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(r) || !aligned16(o) || !aligned16(m))
+        return SB_ERR_ALIGN;
+    if (sb::decode_workspace_bytes(B, H, T, d) > sb::decode_static_bytes()) return SB_ERR_WORKSPACE;
+    float* scratch = nullptr;
+    if (sb::decode_static_scratch(&scratch) != hipSuccess) return SB_ERR_LAUNCH;
+    hipError_t e = sb::launch_decode(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                                     static_cast<const uint16_t*>(v), static_cast<const uint16_t*>(r),
+                                     static_cast<uint16_t*>(o), m, scratch,
+                                     B, H, Hkv, T, Tcap, d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
 int sb_diag_mfma_rate(const void* operands, size_t operand_bytes, int iters, unsigned long long* ticks,
                       double* flop, void* stream)
 {

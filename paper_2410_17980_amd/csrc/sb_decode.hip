@@ -15,8 +15,10 @@
 //       softplus, suffix sums over the chunk, weights, weighted sum of the V rows.
 //   decode_combine_kernel  one workgroup per (batch entry, query head): suffix sums of the
 //       a_s over the chunks, O = sum_s 2^-A_s O_s, optional remainder bias, store.
+#include <mutex>
 #include <type_traits>
 
+#include "../../include/sb_attn.h"
 #include "sb_kernels.h"
 #include "sb_mma.h"
 
@@ -304,9 +306,39 @@ int chunk_keys(int BHkv, int T)
     return C;
 }
 
+// Scratch of the entry point that allocates nothing: every GPU the library runs on holds its
+// own copy of this array, at its own address, until the process ends.  Host code never uses
+// the array's name as a pointer: the device address is looked up once per device.
+constexpr size_t DEC_STATIC_BYTES = SB_DECODE_STATIC_BYTES;
+static __device__ __align__(256) unsigned char scratch[DEC_STATIC_BYTES];
+
+constexpr int DEC_MAX_DEVICES = 64;
+std::mutex scratch_lock;
+void* scratch_ptr[DEC_MAX_DEVICES];        // device address of `scratch`, per device, once known
+
 }  // namespace
 
 int decode_max_T() { return DEC_MAXCHUNKS * DEC_CMAX; }
+
+size_t decode_static_bytes() { return DEC_STATIC_BYTES; }
+
+hipError_t decode_static_scratch(float** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= DEC_MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> guard(scratch_lock);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        scratch_ptr[dev] = p;
+    }
+    *out = static_cast<float*>(scratch_ptr[dev]);
+    return hipSuccess;
+}
 
 size_t decode_workspace_bytes(int B, int H, int T, int d)
 {

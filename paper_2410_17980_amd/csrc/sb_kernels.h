@@ -53,6 +53,11 @@ hipError_t launch_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v
                          uint16_t* o, float* m, float* workspace,
                          int B, int H, int Hkv, int T, int Tcap, int d, hipStream_t stream);
 
+// The library's own decode scratch (a file-scope device array, one copy per GPU): its size,
+// and its device address on the current device (looked up on the first call per device).
+size_t decode_static_bytes();
+hipError_t decode_static_scratch(float** out);
+
 // MFMA-only diagnostic: operands = at least 1 MiB of bf16 on the device, ticks = 3 x u64 on the device
 hipError_t launch_diag_mfma(const void* operands, int iters, unsigned long long* ticks, hipStream_t stream);
 double diag_mfma_flop(int iters);
