@@ -817,27 +817,42 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 // There one wave that holds both accumulators (128 registers) and both stationary operands
 // (64) fills a SIMD's register file alone, and a lone wave cannot hide its own latencies.
 // Here the two waves of a strip split the work so that each needs one accumulator only:
-//   - each takes one 32-query subtile of every 64-row tile through S^T, P^T and the
-//     element-wise path ("front") and writes A and dZ (bf16) row-wise into the strip's LDS
-//     scratch;
-//   - after a workgroup barrier, role 0 accumulates dV += A^T dO and role 1 accumulates
-//     dK += dZ^T Q over both subtiles ("back"), reading the transposed operands from the
-//     scratch.
-// No arithmetic is duplicated; the price is a second barrier per tile.  Two waves per SIMD.
-// (Taking turns instead - one wave of a strip in the element-wise part while the other
-// accumulates - was measured too and is much slower: two waves share the vector ALU better
-// than one wave uses it alone.)
+//   - "front": each takes one 32-query subtile of every 64-row tile through S^T, P^T and the
+//     element-wise path and writes A and dZ (bf16) row-wise into the strip's LDS scratch;
+//   - "back": role 0 accumulates dV += A^T dO and role 1 accumulates dK += dZ^T Q over both
+//     subtiles, reading the transposed operands from the scratch.
+// No arithmetic is duplicated.  The back of a tile is taken one barrier interval after its
+// front, together with the front of the next tile: one workgroup barrier per tile, and in the
+// steady state a wave's interval is one block of code in which the matrix instructions of the
+// back are issued between the vector instructions of the front's element-wise path (step()).
+// Price: the Q/dO tile of the interval before must stay in LDS (three tile buffers) and the
+// A/dZ scratch is double buffered; with compact scratch rows (64 B, xor-swizzled) that is
+// exactly the 160 KB of a CU at d = 128.  Two waves per SIMD.
+// Measured against the predecessor of this kernel (front and back as two phases with a
+// barrier each, padded scratch rows): 1.35 -> 1.29 ms at B8 H16 T4096.  Also measured:
+// the two roles taking front and back in opposite order within an interval (so that one
+// wave of a SIMD is in its vector phase while the other is in its matrix phase) is slower,
+// 1.47 ms: the compiler then copies the accumulator (64 registers) on every switch.
 constexpr int NW2 = 8;
 constexpr int NTHREADS2 = 64 * NW2;
 
-template <int D> struct Dkv2Cfg {
-    static constexpr int T_OFF = 2 * StageCfg<D>::STAGE;   // after the double buffer
-    static constexpr int T_SLOT = 32 * TROW;               // one 32x32 bf16 matrix, padded rows
-    static constexpr int T_STRIP = 4 * T_SLOT;             // [subtile][A, dZ]
-    static constexpr int LDS_BYTES = T_OFF + (NW2 / 2) * T_STRIP;
-    static constexpr int LOADS = StageCfg<D>::TILE / 1024; // wave-wide 1 KB loads per matrix of a 64-row tile
+template <int D> struct Dkv3Cfg {
+    static constexpr int NBUF = 3;
+    static constexpr int T_OFF = NBUF * StageCfg<D>::STAGE;  // after the tile buffers
+    static constexpr int M_BYTES = 32 * 64;                  // one 32x32 bf16 matrix
+    static constexpr int W_BYTES = 2 * M_BYTES;              // A and dZ of one wave's subtile
+    static constexpr int SCR_BUF = NW2 * W_BYTES;            // the eight waves' subtiles of one tile
+    static constexpr int LDS_BYTES = T_OFF + 2 * SCR_BUF;
+    static constexpr int LOADS = StageCfg<D>::TILE / 1024;
     static constexpr int NPW = (LOADS + NW2 - 1) / NW2;
 };
+
+// byte offset of 16-byte chunk c (0..3) of row `row` of a scratch matrix: 16 lanes writing the
+// same chunk of 16 consecutive rows, and 32 lanes reading four whole rows, each touch every bank once
+__device__ __forceinline__ int scr_off(int row, int c)
+{
+    return row * 64 + ((c ^ ((row >> 2) & 3)) << 4);
+}
 
 template <int D, bool SLOW, bool GQA, bool VL>
 __global__ void __launch_bounds__(NTHREADS2, 1)
@@ -848,10 +863,10 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                     int T_arg, int BH, int H, int G_arg, int nkb_arg, int nt32, const int* __restrict__ cu, int Ttot)
 {
     using C = StageCfg<D>;
-    using CK = Dkv2Cfg<D>;
+    using CK = Dkv3Cfg<D>;
+    static_assert(CK::LDS_BYTES <= 160 * 1024, "LDS budget");
     const int G = GQA ? G_arg : 1;                      // query heads per kv head
     __shared__ __attribute__((aligned(1024))) char smem[CK::LDS_BYTES];
-    __shared__ int s_dirty;
 
     const int wg = blockIdx.x;
     const int xcd = wg & 7, slot = wg >> 3;
@@ -868,7 +883,6 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     const int n = lane & 31, hh = lane >> 5;
     const int gg = lane >> 4, li = lane & 15;
 
-    // bh counts kv heads here (BH = B * H / G of them)
     KvHead kh;
     if (!kv_head<D, VL>(kh, bh, pidx, T_arg, nkb_arg, H, G, nt32, cu, Ttot)) return;
     const int T = kh.T, nkb = kh.nkb;
@@ -877,27 +891,26 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     const uint16_t* Qg = nullptr;
     const uint16_t* Gg = nullptr;
 
-    // per-lane LDS offsets inside a 32-row Q / dO subtile (natural row order)
-    int boff[D / 16];                       // B-operand reads: row = query n
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s) boff[s] = tile_off_nat<D>(n, 2 * s + hh);
-    int qtr[D / 32][2];                     // transposing reads (K-dim = queries)
+    // Per-lane LDS offsets inside a 32-row Q / dO subtile.  The swizzle xors the chunk index,
+    // and the chunk indices a lane reads differ in bits the swizzle leaves alone, so one
+    // offset per access pattern is kept and the others follow by xor with a constant:
+    //   B-operand read of chunk pair s (row = query n):        boff0 ^ (s << 5)
+    //   transposing read of column block b, row group t:       qtr0[t] ^ (b << 6)
+    const uint32_t boff0 = tile_off_nat<D>(n, hh);
+    uint32_t qtr0[2];
     {
         const int row_l = 8 * (gg >> 1) + (li >> 2);
         const int cl = 2 * (gg & 1) + ((li & 3) >> 1);
 #pragma unroll
-        for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-                qtr[b][t] = tile_off_nat<D>(row_l + 4 * t, 4 * b + cl) + 8 * (li & 1);
+        for (int t = 0; t < 2; ++t) qtr0[t] = tile_off_nat<D>(row_l + 4 * t, cl) + 8 * (li & 1);
     }
-    // staging: load i of a matrix (1 KB, rows i*BLK_ROWS ..) goes to wave i % 8
     int goff[CK::NPW];
 #pragma unroll
     for (int i = 0; i < CK::NPW; ++i) {
         const int row = (wave + NW2 * i) * C::BLK_ROWS + lane / C::CPR;
         goff[i] = (row * D + (((lane % C::CPR) ^ swz_nat<D>(row)) << 3)) * 2;
     }
+    const uint32_t smem0 = lds_offset(smem);
     auto stage = [&](int jt, char* sp) __attribute__((always_inline)) {
         if ((jt + 1) * TK <= T) {                           // all 64 rows exist
             const uint16_t* xb = Qg + (long)jt * TK * D;
@@ -920,9 +933,15 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                 }
         }
     };
-    char* const scr = smem + CK::T_OFF + strip * CK::T_STRIP;             // [subtile][A, dZ][32][TROW]
-    const int sw_off = n * TROW + 32 * hh;                                // scratch write: row = query n
-    const int st_off = (8 * (gg >> 1) + (li >> 2)) * TROW + (16 * (gg & 1) + 4 * (li & 3)) * 2;
+    // scratch: [tile parity][strip][subtile][A, dZ][32 rows of 64 B]
+    const uint32_t scr = smem0 + CK::T_OFF + strip * 2 * CK::W_BYTES;
+    const uint32_t sw_off = scr_off(n, 2 * hh);                                  // writes: row = query n; second chunk: ^ 16
+    uint32_t st_off[2];                                                          // transposing reads
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int row = 8 * (gg >> 1) + (li >> 2) + 4 * t;
+        st_off[t] = scr_off(row, 2 * (gg & 1) + ((li & 3) >> 1)) + 8 * (li & 1);
+    }
 
     const float scale = 1.0f / sqrtf((float)D);
     const float c2 = SB_LOG2E * scale;
@@ -934,18 +953,20 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     bool dirty = false;                     // a chain of this lane left its range (fast variant)
 
     // this wave's subtile of a tile: logits, dO.v, element-wise path; A and dZ to the scratch
-    auto front = [&](auto mask_c, const char* qtile, float car, float cbl) __attribute__((always_inline)) {
+    // qtile: LDS address of the subtile's Q rows (its dO rows lie C::TILE further); sc: LDS
+    // address of this strip's scratch for the tile
+    auto front = [&](auto mask_c, uint32_t qtile, uint32_t sc, float car, float cbl) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_c)::value;
         if (MASK && n == 0) {               // sees none of the subtile's keys; its carries may be unwritten
             car = 0.0f;
             cbl = 0.0f;
         }
-        const char* gtile = qtile + C::TILE;
+        const uint32_t qa = qtile + boff0;
         u32x4 qw[D / 16], gw[D / 16];
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) {
-            qw[s] = *reinterpret_cast<const u32x4*>(qtile + boff[s]);
-            gw[s] = *reinterpret_cast<const u32x4*>(gtile + boff[s]);
+            qw[s] = lds_load16(qa ^ (s << 5));
+            gw[s] = lds_load16((qa ^ (s << 5)) + C::TILE);
         }
         f32x16 sacc, pacc;
 #pragma unroll
@@ -963,31 +984,70 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             dirty |= !subtile_stage1<MASK, true>(ch, sacc, c2, n, hh);
             subtile_stage2<false, true>(so, ch, pacc, car, cbl, hh);
         }
-        char* w = scr + role * 2 * CK::T_SLOT + sw_off;
-        *reinterpret_cast<bf16x8*>(w) = so.pa[0];
-        *reinterpret_cast<bf16x8*>(w + 16) = so.pa[1];
-        *reinterpret_cast<bf16x8*>(w + CK::T_SLOT) = so.pz[0];
-        *reinterpret_cast<bf16x8*>(w + CK::T_SLOT + 16) = so.pz[1];
+        const uint32_t w = sc + role * CK::W_BYTES + sw_off;
+        lds_store16(w, so.pa[0]);
+        lds_store16(w ^ 16, so.pa[1]);
+        lds_store16(w + CK::M_BYTES, so.pz[0]);
+        lds_store16((w ^ 16) + CK::M_BYTES, so.pz[1]);
     };
-    // this wave's accumulator += (A or dZ of subtile u)^T (dO or Q rows of subtile u)
-    auto back = [&](const char* tile, int u) __attribute__((always_inline)) {
-        const char* m = scr + (2 * u + role) * CK::T_SLOT + st_off;
-        const char* x = tile + (role == 0 ? C::TILE : 0) + u * 32 * C::ROW;
+    // this wave's accumulator += (A or dZ of subtile u)^T (dO or Q rows of subtile u);
+    // tile, sc: LDS addresses of the tile buffer and of this strip's scratch for the tile
+    auto back = [&](uint32_t tile, uint32_t sc, int u) __attribute__((always_inline)) {
+        const uint32_t m = sc + u * CK::W_BYTES + role * CK::M_BYTES;
+        const uint32_t x = tile + (role == 0 ? C::TILE : 0) + u * 32 * C::ROW;
+        const uint32_t x0 = x + qtr0[0], x1 = x + qtr0[1];
         bf16x8 mt[2], op[D / 16];
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) mt[s2] = tr_pair(m + (16 * s2) * TROW, m + (16 * s2 + 4) * TROW);
+        for (int s2 = 0; s2 < 2; ++s2) mt[s2] = tr_pair_at(m + st_off[0] + (16 * s2) * 64, m + st_off[1] + (16 * s2) * 64);
 #pragma unroll
         for (int b = 0; b < D / 32; ++b)
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
                 const int ro = (16 * s2) * C::ROW;
-                op[2 * b + s2] = tr_pair(x + ro + qtr[b][0], x + ro + qtr[b][1]);
+                op[2 * b + s2] = tr_pair_at((x0 ^ (b << 6)) + ro, (x1 ^ (b << 6)) + ro);
             }
 #pragma unroll
         for (int b = 0; b < D / 32; ++b)
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2)
                 acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mt[s2], op[2 * b + s2], acc[b], 0, 0, 0);
+    };
+
+    // front of this wave's subtile (Q rows at qtile) and back of the tile before (buffer ptile,
+    // scratch scp), unmasked and complete, written as one block so that the matrix
+    // instructions of one part can be issued between the vector instructions of the other
+    auto step = [&](uint32_t qtile, uint32_t sc, uint32_t ptile, uint32_t scp, float car, float cbl) __attribute__((always_inline)) {
+        const uint32_t qa = qtile + boff0;
+        // phase A: logits
+        u32x4 qw[D / 16], gw[D / 16];
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) qw[s] = lds_load16(qa ^ (s << 5));
+        f32x16 sacc, pacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; pacc[r] = 0.0f; }
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s)
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], __builtin_bit_cast(bf16x8, qw[s]), sacc, 0, 0, 0);
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) gw[s] = lds_load16((qa ^ (s << 5)) + C::TILE);
+        __builtin_amdgcn_sched_barrier(0);
+        // phase B: the chain of the logits (vector) beside dO.v and the back of subtile 0 (matrix)
+        Chain ch;
+        dirty |= !subtile_stage1<false, true>(ch, sacc, c2, n, hh);
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s)
+            pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s], __builtin_bit_cast(bf16x8, gw[s]), pacc, 0, 0, 0);
+        back(ptile, scp, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        // phase C: A, G, dZ (vector) beside the back of subtile 1 (matrix)
+        SubtileOut so;
+        subtile_stage2<false, true>(so, ch, pacc, car, cbl, hh);
+        back(ptile, scp, 1);
+        const uint32_t w = sc + role * CK::W_BYTES + sw_off;
+        lds_store16(w, so.pa[0]);
+        lds_store16(w ^ 16, so.pa[1]);
+        lds_store16(w + CK::M_BYTES, so.pz[0]);
+        lds_store16((w ^ 16) + CK::M_BYTES, so.pz[1]);
     };
 
     for (int part = 0; part < 2; ++part) {
@@ -998,7 +1058,6 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         const int k0 = K0 + strip * 32;                      // the strip's 32 keys
         const int kt32 = k0 >> 5;
         const bool live = k0 < T;
-        if (tid == 0) s_dirty = 0;
         dirty = false;
         barrier_lds();                                       // everyone is done with the LDS of the block before
         {
@@ -1027,10 +1086,11 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         cbg = cb + cbase + g * cbase_step + kt32 * cstride;
         if (g > 0) barrier_lds();                            // everyone is done with the LDS of the head before
 
-        // ---- sweep over 64-row query tiles, from the block's diagonal to the end;
-        // iteration it handles tile jt0 + it in buffer it & 1.  The carries of this wave's
-        // subtile are fetched one iteration ahead, and BEFORE the staging loads of that
-        // iteration are issued (vector memory operations complete in order).
+        // ---- sweep over 64-row query tiles, from the block's diagonal to the end.  Interval
+        // `it` (between two barriers) holds the front of tile jt0 + it (buffer it % 3, scratch
+        // it & 1) and the back of tile jt0 + it - 1; the staging loads of tile jt0 + it + 1 are
+        // issued at its start, after the carries of that tile (vector memory operations
+        // complete in order, so the carries must not queue behind the staging loads).
         const int jt0 = K0 / TK;
         const int ntile = max((T + TK - 1) / TK - jt0, 0);
         const int ndiag = min(ntile, BKW / TK);              // tiles that touch the diagonal band
@@ -1045,31 +1105,41 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             load_carries(jt0);
             stage(jt0, smem);
         }
-        for (int it = 0; it < ntile; ++it) {
+        int bcur = 0, bprev = 2, bnext = 1;                  // tile buffers of tiles it, it - 1, it + 1
+        for (int it = 0; it <= ntile; ++it) {
+            if (it > 0) { bprev = bcur; bcur = bnext; bnext = bcur == 2 ? 0 : bcur + 1; }
             dma_wait<0>();
-            barrier_lds();                                   // tile `it` has landed; tile it-1 and its scratch are free
+            barrier_lds();        // tile `it` has landed, the scratch of tile it-1 is complete, tile it-2 is free
             const float car = cn0, cbl = cn1;
             if (it + 1 < ntile) {
                 load_carries(jt0 + it + 1);
-                stage(jt0 + it + 1, smem + ((it + 1) & 1) * C::STAGE);
+                stage(jt0 + it + 1, smem + bnext * C::STAGE);
             }
-            const char* sp = smem + (it & 1) * C::STAGE;
             const int jbase = (jt0 + it) * TK;
-            const int j0 = jbase + 32 * role;                // this wave's subtile
-            if (live && j0 < T) {
-                if (it < ndiag) {
-                    if (j0 == k0) front(bc<true>{}, sp + role * 32 * C::ROW, car, cbl);
-                    else if (j0 > k0) front(bc<false>{}, sp + role * 32 * C::ROW, car, cbl);
-                } else {
-                    front(bc<false>{}, sp + role * 32 * C::ROW, car, cbl);
+            const uint32_t qt = smem0 + bcur * C::STAGE + role * 32 * C::ROW;
+            const uint32_t sc = scr + (it & 1) * CK::SCR_BUF;
+            const uint32_t spp = smem0 + bprev * C::STAGE;
+            const uint32_t scp = scr + ((it + 1) & 1) * CK::SCR_BUF;
+            if (!SLOW && live && it > ndiag && it < ntile && jbase + TK <= T) {
+                // steady state: the front of this wave's subtile of tile `it` and the back of
+                // tile it - 1 as one stream of independent matrix and vector work
+                step(qt, sc, spp, scp, car, cbl);
+            } else {
+                const int j0 = jbase + 32 * role;
+                if (it < ntile && live && j0 < T) {
+                    if (it < ndiag) {
+                        if (j0 == k0) front(bc<true>{}, qt, sc, car, cbl);
+                        else if (j0 > k0) front(bc<false>{}, qt, sc, car, cbl);
+                    } else {
+                        front(bc<false>{}, qt, sc, car, cbl);
+                    }
                 }
-            }
-            barrier_lds();                                   // both subtiles' A and dZ are in the scratch
-            if (live) {
+                if (it >= 1 && live) {
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int ju = jbase + 32 * u;
-                    if (ju >= k0 && ju < T) back(sp, u);
+                    for (int u = 0; u < 2; ++u) {
+                        const int ju = jbase - TK + 32 * u;
+                        if (ju >= k0 && ju < T) back(spp, scp, u);
+                    }
                 }
             }
         }
@@ -1089,9 +1159,14 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             }
         }
         if constexpr (!SLOW) {
-            if (__builtin_amdgcn_ballot_w64(dirty) != 0 && lane == 0) atomicOr(&s_dirty, 1);
+            // the block's flag: any chain of any wave out of range.  The tile buffers are free by now.
+            int* s_dirty = reinterpret_cast<int*>(smem);
+            barrier_lds();
+            if (tid == 0) *s_dirty = 0;
             __syncthreads();
-            if (tid == 0) flags[bh * nkb_arg + kb] = s_dirty;
+            if (__builtin_amdgcn_ballot_w64(dirty) != 0 && lane == 0) atomicOr(s_dirty, 1);
+            __syncthreads();
+            if (tid == 0) flags[bh * nkb_arg + kb] = *s_dirty;
         }
     }
 }

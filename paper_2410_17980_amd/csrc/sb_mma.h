@@ -98,6 +98,24 @@ __device__ __forceinline__ uint32_t lds_offset(const char* p)
     return (uint32_t)(uintptr_t)p;
 }
 
+// LDS accesses by 32-bit LDS byte address (integer arithmetic on addresses, xor included,
+// stays in the LDS address space this way)
+typedef __attribute__((address_space(3))) const u32x4* lds_cu32x4_ptr;
+typedef __attribute__((address_space(3))) u32x4* lds_u32x4_ptr;
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+__device__ __forceinline__ u32x4 lds_load16(uint32_t addr) { return *(lds_cu32x4_ptr)(uintptr_t)(addr); }
+__device__ __forceinline__ void lds_store16(uint32_t addr, bf16x8 v)
+{
+    *(lds_u32x4_ptr)(uintptr_t)(addr) = __builtin_bit_cast(u32x4, v);
+}
+// tr_pair by LDS address
+__device__ __forceinline__ bf16x8 tr_pair_at(uint32_t a_lo, uint32_t a_hi)
+{
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)(a_lo));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)(a_hi));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
 // Direct global -> LDS copy of 16 bytes per lane (global_load_lds_dwordx4): lane l
 // of the wave writes LDS bytes [lds_base + 16 l, +16) with the 16 bytes at its own
 // global address; lds_base must be wave-uniform.  Issued through inline assembly so
