@@ -294,23 +294,20 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* Kg = k + kvbase;
     const uint16_t* Vg = v + kvbase;
 
-    // per-lane LDS offsets inside a 32-row subtile
-    int aoff[D / 16];                       // A-operand reads (K rows for S^T, V rows for P^T)
-    {
-        const int key_l = perm_row(n);
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) aoff[s] = tile_off_perm<D>(key_l, 2 * s + hh);
-    }
-    int ktr[D / 32][2];                     // transposing reads of K for dQ = dZ K
+    // Per-lane LDS offsets inside a 32-row subtile.  The swizzle xors the chunk index, and the
+    // chunk indices a lane reads differ in bits the swizzle leaves alone, so one offset per
+    // access pattern is kept and the others follow by xor with a constant:
+    //   A-operand read of chunk pair s (K rows for S^T, V rows for P^T):  aoff0 ^ (s << 5)
+    //   transposing read of K, column block b, row group t (dQ = dZ K):    ktr0[t] ^ (b << 6)
+    const uint32_t aoff0 = tile_off_perm<D>(perm_row(n), hh);
+    uint32_t ktr0[2];
     {
         const int row_l = 16 * (gg >> 1) + (li >> 2);
         const int cl = 2 * (gg & 1) + ((li & 3) >> 1);
 #pragma unroll
-        for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-                ktr[b][t] = tile_off_perm<D>(row_l + 4 * t, 4 * b + cl) + 8 * (li & 1);
+        for (int t = 0; t < 2; ++t) ktr0[t] = tile_off_perm<D>(row_l + 4 * t, cl) + 8 * (li & 1);
     }
+    const uint32_t smem0 = lds_offset(smem);
     int goff[C::NPW];
     stage_offsets<D, true>(goff, wave, lane);
 
@@ -327,15 +324,16 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     bool dirty = false;                     // a chain of this lane left its range (fast variant)
 
     // one 32-key subtile at keys key0 .. key0+31
-    auto subtile = [&](auto mask_c, const char* ktile, int key0) __attribute__((always_inline)) {
+    // ktile: LDS address of the subtile's K rows (its V rows lie C::TILE further)
+    auto subtile = [&](auto mask_c, uint32_t ktile, int key0) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_c)::value;
-        const char* vtile = ktile + C::TILE;
+        const uint32_t ka = ktile + aoff0;
         // the operand reads of a product are issued before its first MFMA: the LDS latency
         // is then paid once per product, not once per MFMA
         auto s_mfma = [&]() __attribute__((always_inline)) {
             u32x4 kw[D / 16];
 #pragma unroll
-            for (int s = 0; s < D / 16; ++s) kw[s] = *reinterpret_cast<const u32x4*>(ktile + aoff[s]);
+            for (int s = 0; s < D / 16; ++s) kw[s] = lds_load16(ka ^ (s << 5));
             f32x16 acc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
@@ -347,7 +345,7 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         auto p_mfma = [&]() __attribute__((always_inline)) {
             u32x4 vw[D / 16];
 #pragma unroll
-            for (int s = 0; s < D / 16; ++s) vw[s] = *reinterpret_cast<const u32x4*>(vtile + aoff[s]);
+            for (int s = 0; s < D / 16; ++s) vw[s] = lds_load16((ka ^ (s << 5)) + C::TILE);
             f32x16 acc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
@@ -378,12 +376,13 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         bsum += so.g_tot;
         // dQ += dZ K: dZ from registers, K (rows = keys) through the transposing load
         bf16x8 kt[D / 16];
+        const uint32_t k0a = ktile + ktr0[0], k1a = ktile + ktr0[1];
 #pragma unroll
         for (int b = 0; b < D / 32; ++b)
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const char* p = ktile + (8 * s) * C::ROW;
-                kt[2 * b + s] = tr_pair(p + ktr[b][0], p + ktr[b][1]);
+                const int ro = (8 * s) * C::ROW;
+                kt[2 * b + s] = tr_pair_at((k0a ^ (b << 6)) + ro, (k1a ^ (b << 6)) + ro);
             }
 #pragma unroll
         for (int b = 0; b < D / 32; ++b)
@@ -454,16 +453,16 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             barrier_nofence();                           // ... everyone's has, and tile it-1 is no longer read
             // past the end tile 0 is loaded once more into the buffer nobody reads
             stage_tile<D, true>(Kg, Vg, it + 1 < ntile ? it + 1 : 0, T, smem + ((it + 1) & 1) * C::STAGE, goff, wave, lane);
-            return (const char*)(smem + (it & 1) * C::STAGE);
+            return smem0 + (it & 1) * C::STAGE;
         };
         int it = 0;
         for (; it < nclean; ++it) {                      // fully visible tiles
-            const char* sp = begin_iter(it);
+            const uint32_t sp = begin_iter(it);
             subtile(bc<false>{}, sp, it * TK);
             subtile(bc<false>{}, sp + 32 * C::ROW, it * TK + 32);
         }
         for (; it < ntile; ++it) {                       // tiles that touch the diagonal band
-            const char* sp = begin_iter(it);
+            const uint32_t sp = begin_iter(it);
             if (wave_live) {
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
