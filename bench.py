@@ -8,9 +8,12 @@ workload (bf16, B=8, H=16, T=4096, d_head=128; half the heads with k*3): the
 training forward (o and m) followed by the backward (dq, dk, dv).  Inputs are
 resident in HBM before the timed region starts.  One JSON line is printed:
 whole-step TFLOP/s as `value`, the forward and the two backward passes separately,
-a roofline object for the dominant kernel, the rate the matrix cores sustain on
-such data with no other work (the practical ceiling under the power limit) and
-the CPU oracle timed on a bounded sample.
+a roofline object for the dominant kernel, every one of the five stated
+workloads with its own timing and its error against the CPU oracle (`configs`),
+the rate the matrix cores sustain on such data with no other work (the practical
+ceiling under the power limit), the vendor GEMM at a large square shape and the
+shader clock the forward ran at for context, and the CPU oracle timed on a
+bounded sample.
 
 FLOP convention (algorithmic, strictly causal pairs only): one contraction is
 2*d FLOP per (query, key) pair with key < query; forward = 2 contractions,
@@ -20,7 +23,9 @@ dK, dV = 2, its recomputation of the first two is not counted).  Nothing else
 
 `roofline.traffic` (HBM bytes per launch of the dominant kernel) comes from
 rocprofv3 counter runs that cannot be made from inside this script; it is read
-from profiles/hbm_traffic_B8_H16_T4096_d128.txt when that file is present.
+from profiles/hbm_traffic_B8_H16_T4096_d128.txt (named in `traffic_source`) when
+that file is present.  It is a stored measurement of the kernel as it was when the
+profile was taken, not of this run.
 """
 from __future__ import annotations
 
@@ -49,6 +54,8 @@ def event_time_ms(fn, iters):
     """Average duration of fn() over iters back-to-back launches, HIP events on
     the stream the kernels are launched on (torch's current stream)."""
     import torch
+    for _ in range(2):                     # first use of a kernel pays for loading it
+        fn()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     e0.record()
@@ -119,6 +126,106 @@ def cpu_baseline(w, q, k, v, dout, n_heads, with_bwd):
     }
 
 
+def launch_stats(fn, iters):
+    """Mean over back-to-back launches plus median and minimum of individually timed ones."""
+    ms = event_time_ms(fn, iters)
+    return {"ms": ms, **spread(event_times_ms(fn, iters))}
+
+
+def config_entries(sb, inputs, iters, headline):
+    """The five stated workloads, each with its own launch timing (HIP events, >= 50
+    launches) and its max abs error against the float64 oracle on the slices the
+    workload states.  headline: (tensors, stats) of workload 3, measured by the caller."""
+    import numpy as np
+    import torch
+    from oracle import sb_oracle
+    sb_oracle.build()
+    f64 = lambda t: t.detach().cpu().to(torch.float32).to(torch.float64).numpy()
+    out = []
+    for idx, w in enumerate(inputs.WORKLOADS):
+        B, H, T, d = w.B, w.H, w.T, w.d
+        e = {"config": idx + 1, "workload": w.name, "B": B, "H": H, "T": T, "d_head": d, "dtype": w.dtype,
+             "pass": w.direction}
+        if idx == 2:
+            (q, k, v, _), st, od = headline
+            qd = kd = vd = None
+        else:
+            ts = inputs.workload_tensors(w)
+            q, k, v = ts[:3]
+            qd, kd, vd = (t.cuda() for t in (q, k, v))
+        if w.direction == "fwd":
+            flop = flops_fwd(B, H, T, d)
+            if w.dtype == "f32":
+                od = torch.empty_like(qd)
+                fn = lambda: sb.sb_attn_fwd_f32(qd, kd, vd, od)
+                e["entry"], tol = "sb_attn_fwd_f32", 1e-5
+            elif idx == 4:
+                od = torch.empty_like(qd)
+                fn = lambda: sb.sb_attn_fwd(qd, kd, vd, od)
+                e["entry"], tol = "sb_attn_fwd", 2e-2
+            elif idx != 2:
+                od = torch.empty_like(qd)
+                md = torch.empty((B, H, T), dtype=torch.float32, device="cuda")
+                fn = lambda: sb.sb_attn_fwd_train(qd, kd, vd, od, md)
+                e["entry"], tol = "sb_attn_fwd_train", 2e-2
+            else:
+                e["entry"], tol = "sb_attn_fwd_train", 2e-2
+            if idx != 2:
+                fn()
+                st = launch_stats(fn, iters)
+            # oracle check on the stated slices
+            if idx == 0:
+                ref, _ = sb_oracle.fwd(f64(q), f64(k), f64(v))
+                err = float(np.abs(f64(od) - ref).max())
+                e["checked"] = "all rows"
+            elif idx == 4:
+                picks, r0 = inputs.slice_picks(w, 2), T - 512
+                err = 0.0
+                for b, h in picks:
+                    ref, _ = sb_oracle.fwd(f64(q[b, h]), f64(k[b, h]), f64(v[b, h]), rows=(r0, T))
+                    err = max(err, float(np.abs(f64(od[b, h, r0:]) - ref).max()))
+                e["checked"] = "2 heads, last 512 rows"
+            else:
+                picks = inputs.slice_picks(w, 4)
+                err = 0.0
+                for b, h in picks:
+                    ref, _ = sb_oracle.fwd(f64(q[b, h]), f64(k[b, h]), f64(v[b, h]))
+                    err = max(err, float(np.abs(f64(od[b, h]) - ref).max()))
+                e["checked"] = "4 (b,h) slices" + (", 2 of them sharp heads" if w.sharp_half else "")
+            e["max_abs_err"], e["tol"] = err, tol
+        else:
+            flop = flops_bwd(B, H, T, d)
+            g = ts[3]
+            gd = g.cuda()
+            od, md = sb.sb_attn_fwd_train(qd, kd, vd)
+            dq = torch.empty((B, H, T, d), dtype=torch.float32, device="cuda")
+            dk, dv = torch.empty_like(dq), torch.empty_like(dq)
+            ws = torch.empty(sb.sb_attn_bwd_workspace_bytes(B, H, T, d), dtype=torch.uint8, device="cuda")
+            fn = lambda: sb.sb_attn_bwd(qd, kd, vd, md, gd, dq, dk, dv, ws)
+            fn()
+            st = launch_stats(fn, iters)
+            e["entry"] = "sb_attn_bwd"
+            picks = inputs.slice_picks(w, 4)
+            errs = {"dq": 0.0, "dk": 0.0, "dv": 0.0}
+            rels = {"dq": 0.0, "dk": 0.0, "dv": 0.0}
+            for b, h in picks:
+                refs = sb_oracle.bwd(f64(q[b, h]), f64(k[b, h]), f64(v[b, h]), f64(g[b, h]))
+                for name, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), refs):
+                    err1 = float(np.abs(f64(got[b, h]) - ref).max())
+                    errs[name] = max(errs[name], err1)
+                    rels[name] = max(rels[name], err1 / float(np.abs(ref).max()))
+            e["checked"] = "4 (b,h) slices, analytic gradients"
+            e["max_abs_err"], e["tol"] = max(errs.values()), 2e-2
+            e["max_abs_err_by_tensor"], e["max_err_over_max_ref"] = errs, rels
+        tf = flop / (st["ms"] * 1e-3) / 1e12
+        e.update({"flop": flop, **st, "tflops": tf, "frac_bf16_peak": tf / PEAK_BF16_TFLOPS,
+                  "ok": bool(e["max_abs_err"] <= e["tol"])})
+        if w.dtype == "f32":
+            e["note"] = "vector-ALU fp32 check path, latency-bound at this size: not a matrix-core rate"
+        out.append(e)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -128,6 +235,7 @@ def main():
     ap.add_argument("--kernel-iters", type=int, default=50, help="launches per kernel for the event timing")
     ap.add_argument("--passes", choices=["fwd", "fwd+bwd"], default=DEFAULT_PASSES,
                     help="what one step runs")
+    ap.add_argument("--no-configs", action="store_true", help="skip the per-workload `configs` array")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB element-wise copy kernel (3 times): the known traffic the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by")
@@ -191,6 +299,7 @@ def main():
     ms_fwd = event_time_ms(fwd, args.kernel_iters)
     sp_fwd = spread(event_times_ms(fwd, args.kernel_iters))
     tf_fwd = f_fwd / (ms_fwd * 1e-3) / 1e12
+    o_fwd = o.clone()                      # the headline forward's output, checked against the oracle below
     kernels = {"fwd_bf16_kernel": (ms_fwd, f_fwd)}
     if with_bwd:
         ms_bwd = event_time_ms(bwd, args.kernel_iters)
@@ -231,10 +340,29 @@ def main():
     wsd = torch.empty(sb.load().sb_attn_decode_workspace_bytes(B, H, Td, d), dtype=torch.uint8, device="cuda")
     ms_dec = event_time_ms(lambda: sb.sb_attn_decode(q1, kc, vc, o=o1, workspace=wsd), 3 * args.kernel_iters)
     dec_bytes = 2.0 * B * H * Td * d * 2
-    del kc, vc
+    # what a kernel that only reads the same number of bytes reaches (K and V together)
+    kv_all = torch.cat([kc.reshape(-1), vc.reshape(-1)])
+    stream_gbs = sb.sb_diag_stream_read(kv_all, iters=20)
+    del kc, vc, kv_all
 
     # the rate the matrix cores sustain on data like the workload's with nothing else running
     mfma_tf, mfma_mhz = sb.sb_diag_mfma_rate(kd.reshape(-1)[: 1 << 21], iters=4000)
+
+    # the shader clock the chip holds while the forward runs (sampled inside the kernel, after
+    # a burst of launches so that the power management has settled)
+    for _ in range(20):
+        fwd()
+    fwd_mhz = sb.sb_diag_fwd_clock(qd, kd, vd, o, m)
+
+    # context: the vendor GEMM (hipBLASLt through torch.mm) on a large square bf16 problem
+    n_g = 8192
+    ga = torch.randn(n_g, n_g, device="cuda", dtype=torch.bfloat16)
+    gb = torch.randn(n_g, n_g, device="cuda", dtype=torch.bfloat16)
+    gc = torch.empty_like(ga)
+    torch.mm(ga, gb, out=gc)
+    ms_gemm = event_time_ms(lambda: torch.mm(ga, gb, out=gc), 20)
+    gemm_tf = 2.0 * n_g ** 3 / (ms_gemm * 1e-3) / 1e12
+    del ga, gb, gc
 
     # dominant kernel = the one with the largest share of the step
     dom = max(kernels, key=lambda n: kernels[n][0])
@@ -254,7 +382,7 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": w.name, "B": B, "H": H, "T": T, "d_head": d,
+        "config": {"workload": "train_step_bf16_B8_H16_T4096_d128", "B": B, "H": H, "T": T, "d_head": d,
                    "inputs": "iid N(0,1) bf16, heads h>=H/2 with k*3, seed 2",
                    "step": "fwd_train + bwd" if with_bwd else "fwd_train", "early_halt": "off"},
         "fwd": {"ms": ms_fwd, "tflops": tf_fwd, "frac_bf16_peak": tf_fwd / PEAK_BF16_TFLOPS, **sp_fwd},
@@ -274,7 +402,13 @@ def main():
                    "roofline": {"bound": "hbm", "achieved": dec_bytes / (ms_dec * 1e-3) / 1e9, "peak": 8000.0,
                                 "unit": "GB/s", "frac": dec_bytes / (ms_dec * 1e-3) / 1e9 / 8000.0,
                                 "bytes_per_launch": dec_bytes, "what": "K and V read once",
-                                "traffic": hbm_traffic("decode_partial_kernel")}},
+                                "traffic": hbm_traffic("decode_partial_kernel"),
+                                "streaming_read_gbs": stream_gbs,
+                                "frac_streaming_read": dec_bytes / (ms_dec * 1e-3) / 1e9 / stream_gbs}},
+        "fwd_shader_clock_mhz": fwd_mhz,
+        "gemm_reference": {"tflops": gemm_tf, "frac_bf16_peak": gemm_tf / PEAK_BF16_TFLOPS, "ms": ms_gemm,
+                           "what": "torch.mm (hipBLASLt), bf16, 8192^3, N(0,1) data: the vendor's dense "
+                                   "contraction on this chip, for context"},
         "mfma_only_ceiling": {"tflops": mfma_tf, "frac_bf16_peak": mfma_tf / PEAK_BF16_TFLOPS,
                               "shader_clock_mhz": mfma_mhz,
                               "what": "32x32x16 bf16 MFMAs alone, operands = the workload's k, 2 waves per SIMD"},
@@ -284,6 +418,11 @@ def main():
     if with_bwd:
         out["bwd"]["frac_mfma_only_ceiling"] = tf_bwd / mfma_tf
     out["roofline"]["frac_mfma_only_ceiling"] = dom_tf / mfma_tf
+    out["roofline"]["traffic_source"] = "profiles/hbm_traffic_B8_H16_T4096_d128.txt (stored rocprofv3 run)"
+    out["fwd"]["frac_gemm_reference"] = tf_fwd / gemm_tf
+    if not args.no_configs:
+        out["configs"] = config_entries(sb, inputs, max(args.kernel_iters, 50),
+                                        ((q, k, v, dout), {"ms": ms_fwd, **sp_fwd}, o_fwd))
     if args.cpu_heads > 0:
         out["cpu_baseline"] = cpu_baseline(w, q, k, v, dout, args.cpu_heads, with_bwd)
     print(json.dumps(out))

@@ -213,18 +213,6 @@ int sb_attn_decode(const void* q, const void* k, const void* v, const void* r, v
 int sb_attn_decode_static(const void* q, const void* k, const void* v, const void* r, void* o, float* m,
                           int B, int H, int Hkv, int T, int Tcap, int d, void* stream);
 
-/*
- * Measurement aid (not part of the method): runs `iters` x 16 independent
- * 32x32x16 bf16 MFMAs per wavefront, two wavefronts per SIMD on the whole chip,
- * on operands taken from `operands` (device, bf16, at least 1 MiB, 16-byte
- * aligned) and nothing else.  The rate it reaches is what the matrix cores
- * sustain on that data under the chip's power limit.  ticks (device, 3 x u64,
- * 16-byte aligned) receives [0] shader clocks and [1] 100 MHz reference ticks of
- * one wavefront's loop; *flop (host) receives the FLOP the launch executes.
- */
-int sb_diag_mfma_rate(const void* operands, size_t operand_bytes, int iters, unsigned long long* ticks,
-                      double* flop, void* stream);
-
 /* Human-readable name of a status code (static storage). */
 const char* sb_status_string(int status);
 

@@ -1,4 +1,4 @@
-"""Thin ctypes binding of libsbattn.so (include/sb_attn.h): same names, argument
+"""Thin ctypes binding of libsbattn.so (include/sb_attn.h, include/sb_diag.h): same names, argument
 marshalling only.  torch is used to own device memory and to name the stream;
 every step of the computation runs inside the library's kernels.
 
@@ -20,7 +20,7 @@ EXPORTS = (
     "sb_attn_fwd_rb", "sb_attn_bwd_rb", "sb_attn_fwd_gqa", "sb_attn_bwd_gqa",
     "sb_attn_varlen_fwd", "sb_attn_varlen_bwd_workspace_bytes", "sb_attn_varlen_bwd",
     "sb_attn_decode_workspace_bytes", "sb_attn_decode", "sb_attn_decode_static",
-    "sb_diag_mfma_rate",
+    "sb_diag_mfma_rate", "sb_diag_stream_read", "sb_diag_fwd_clock",
     "sb_status_string", "sb_version",
 )
 
@@ -83,6 +83,10 @@ def load(build_if_missing: bool = True):
     lib.sb_attn_decode_static.restype = ci
     lib.sb_diag_mfma_rate.argtypes = [vp, ctypes.c_size_t, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.sb_diag_mfma_rate.restype = ci
+    lib.sb_diag_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.sb_diag_stream_read.restype = ci
+    lib.sb_diag_fwd_clock.argtypes = [vp, vp, vp, vp, fp, ci, ci, ci, ci, vp, vp]
+    lib.sb_diag_fwd_clock.restype = ci
     lib.sb_status_string.argtypes = [ci]
     lib.sb_status_string.restype = ctypes.c_char_p
     lib.sb_version.argtypes = []
@@ -447,3 +451,38 @@ def sb_diag_mfma_rate(operands, iters=2000, stream=None):
     t = ticks.cpu().tolist()
     mhz = t[0] / (t[1] / 100e6) / 1e6 if t[1] > 0 else float("nan")
     return flop.value / (ms * 1e-3) / 1e12, mhz
+
+
+def sb_diag_stream_read(data, iters=10, stream=None):
+    """Read bandwidth (GB/s) of a kernel that only loads `data` (any contiguous GPU tensor)."""
+    if not data.is_cuda or not data.is_contiguous():
+        raise SbAttnError("data must be a contiguous tensor on the GPU")
+    nbytes = (data.numel() * data.element_size()) // 16 * 16
+    sink = torch.zeros(4, dtype=torch.int32, device=data.device)
+    run = lambda: _check(load().sb_diag_stream_read(ctypes.c_void_p(data.data_ptr()), nbytes,
+                                                    ctypes.c_void_p(sink.data_ptr()), _stream(stream)),
+                         "sb_diag_stream_read")
+    for _ in range(2):
+        run()
+    s = torch.cuda.current_stream() if stream is None else stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(s)
+    for _ in range(iters):
+        run()
+    e1.record(s)
+    e1.synchronize()
+    return nbytes * iters / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def sb_diag_fwd_clock(q, k, v, o, m, stream=None):
+    """sb_attn_fwd_train that also returns the shader clock (MHz) its first workgroup saw."""
+    B, H, T, d = _dims(q)
+    clocks = torch.zeros(4, dtype=torch.int64, device=q.device)
+    rc = load().sb_diag_fwd_clock(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, q.shape, "k"),
+                                  _ptr(v, torch.bfloat16, q.shape, "v"), _ptr(o, torch.bfloat16, q.shape, "o"),
+                                  _ptr(m, torch.float32, (B, H, T), "m"), B, H, T, d,
+                                  ctypes.c_void_p(clocks.data_ptr()), _stream(stream))
+    _check(rc, "sb_diag_fwd_clock")
+    c = clocks.cpu().tolist()
+    ref = c[3] - c[1]
+    return (c[2] - c[0]) / (ref / 100e6) / 1e6 if ref > 0 else float("nan")

@@ -1,6 +1,7 @@
 // C-ABI entry points: argument validation and dispatch to the kernel launchers.
 // See include/sb_attn.h for the contract of every call.
 #include "../../include/sb_attn.h"
+#include "../../include/sb_diag.h"
 #include "sb_kernels.h"
 
 namespace {
@@ -283,6 +284,28 @@ int sb_diag_mfma_rate(const void* operands, size_t operand_bytes, int iters, uns
     if (!aligned16(operands) || !aligned16(ticks)) return SB_ERR_ALIGN;
     *flop = sb::diag_mfma_flop(iters);
     hipError_t e = sb::launch_diag_mfma(operands, iters, ticks, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
+int sb_diag_stream_read(const void* data, size_t bytes, unsigned int* sink, void* stream)
+{
+    if (!data || !sink) return SB_ERR_NULL;
+    if (bytes < (1u << 20) || bytes % 16 != 0) return SB_ERR_SHAPE;
+    if (!aligned16(data)) return SB_ERR_ALIGN;
+    hipError_t e = sb::launch_diag_stream(data, bytes, sink, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
+int sb_diag_fwd_clock(const void* q, const void* k, const void* v, void* o, float* m,
+                      int B, int H, int T, int d, unsigned long long* clocks, void* stream)
+{
+    if (!q || !k || !v || !o || !m || !clocks) return SB_ERR_NULL;
+    if (int rc = check_shape(B, H, T, d)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(m) || !aligned16(clocks))
+        return SB_ERR_ALIGN;
+    hipError_t e = sb::launch_fwd_bf16(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                                       static_cast<const uint16_t*>(v), nullptr, static_cast<uint16_t*>(o),
+                                       m, B, H, H, T, d, static_cast<hipStream_t>(stream), clocks);
     return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
 }
 

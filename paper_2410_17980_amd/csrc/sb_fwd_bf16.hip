@@ -112,6 +112,15 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if constexpr (!HALT) {
+        // measurement aid: with a non-null tile_counts the first workgroup leaves the shader
+        // clock counter and the 100 MHz reference counter at its start ([0], [1]) and at its end
+        // ([2], [3]); their ratio is the clock the chip sustained while this kernel ran
+        if (tile_counts && wg == 0 && tid == 0) {
+            tile_counts[0] = (unsigned long long)clock64();
+            tile_counts[1] = (unsigned long long)wall_clock64();
+        }
+    }
     const int n = lane & 31;          // query column inside the wave
     const int hh = lane >> 5;         // half-wave: keys 16*hh .. 16*hh+15 of a subtile
     const int gg = lane >> 4, li = lane & 15;
@@ -416,6 +425,12 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             if (WRITE_M && hh == 0 && q0 + n < T) m[row0 + q0 + n] = -a * SB_LN2;
         }
     }
+    if constexpr (!HALT) {
+        if (tile_counts && wg == 0 && tid == 0) {
+            tile_counts[2] = (unsigned long long)clock64();
+            tile_counts[3] = (unsigned long long)wall_clock64();
+        }
+    }
 }
 
 template <int D, bool WRITE_M, bool HALT, bool RB, bool VL = false>
@@ -436,11 +451,12 @@ hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, c
 }  // namespace
 
 hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
-                           uint16_t* o, float* m, int B, int H, int Hkv, int T, int d, hipStream_t stream)
+                           uint16_t* o, float* m, int B, int H, int Hkv, int T, int d, hipStream_t stream,
+                           unsigned long long* clocks)
 {
     const int BH = B * H;
     const int G = H / Hkv;
-#define SB_FWD(DD, WM, RBV) launch_one<DD, WM, false, RBV>(q, k, v, rb, o, m, BH, H, G, T, 0.0f, nullptr, stream)
+#define SB_FWD(DD, WM, RBV) launch_one<DD, WM, false, RBV>(q, k, v, rb, o, m, BH, H, G, T, 0.0f, clocks, stream)
     if (d == 32) {
         if (rb) return m ? SB_FWD(32, true, true) : SB_FWD(32, false, true);
         return m ? SB_FWD(32, true, false) : SB_FWD(32, false, false);

@@ -14,8 +14,11 @@ hipError_t launch_fwd_f32(const float* q, const float* k, const float* v, float*
 
 // rb: remainder-bias embeddings [H][d] bf16, or nullptr; m: nullptr when not wanted.
 // H query heads, Hkv kv heads (H a multiple of Hkv): k, v are [B][Hkv][T][d].
+// clocks: nullptr, or 4 x u64 on the device that receive the shader-clock and 100 MHz reference
+// counters at the start ([0], [1]) and the end ([2], [3]) of the launch's first workgroup.
 hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
-                           uint16_t* o, float* m, int B, int H, int Hkv, int T, int d, hipStream_t stream);
+                           uint16_t* o, float* m, int B, int H, int Hkv, int T, int d, hipStream_t stream,
+                           unsigned long long* clocks = nullptr);
 
 // forward that stops sweeping a query block once every row has less than eps of its stick left
 hipError_t launch_fwd_bf16_halt(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o,
@@ -61,5 +64,7 @@ hipError_t decode_static_scratch(float** out);
 // MFMA-only diagnostic: operands = at least 1 MiB of bf16 on the device, ticks = 3 x u64 on the device
 hipError_t launch_diag_mfma(const void* operands, int iters, unsigned long long* ticks, hipStream_t stream);
 double diag_mfma_flop(int iters);
+// read-only streaming diagnostic: every 16-byte word of [data, data + bytes) is loaded once
+hipError_t launch_diag_stream(const void* data, size_t bytes, unsigned int* sink, hipStream_t stream);
 
 }  // namespace sb
