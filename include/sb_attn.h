@@ -94,6 +94,14 @@ int sb_attn_fwd_f32(const float* q, const float* k, const float* v, float* o, fl
  * d floats per 128-row block (partial sums of sb_attn_bwd_rb's dr):
  * B*H*(8*T*ceil(T/32) + (8 + 4*d)*ceil(T/128)) bytes.  SB_ERR_WORKSPACE if it is NULL or
  * too small.  sb_attn_bwd_workspace_bytes returns 0 for a bad shape.
+ * The carried sums make the workspace grow with T^2 (T^2/4 bytes per head: 4 MiB at
+ * T = 4096, 64 MiB at T = 16384, 1 GiB at T = 65536), where Algorithm 2 itself keeps O(T):
+ * that is the price of writing dK and dV without atomics.  Heads are independent, so a caller
+ * short of memory at long T runs the backward on groups of heads (or batch entries) with one
+ * smaller workspace, one call after the other.
+ * m is required (SB_ERR_NULL otherwise): it is what the training forward of the same step
+ * leaves behind, and rebuilding it here would cost a forward sweep (two of the backward's
+ * seven contractions) that no caller of a backward has reason to pay.
  * No atomics are used: results are bit-reproducible from run to run.
  */
 size_t sb_attn_bwd_workspace_bytes(int B, int H, int T, int d);

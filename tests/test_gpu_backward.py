@@ -2,17 +2,18 @@
 oracle's analytic gradients (themselves pinned by finite differences) on the
 same seeded, already-rounded bf16 inputs.
 
-Tolerance: max abs error max(2e-2, 2^-8 * max|ref|) on each of dq, dk, dv: the
-forward's bound while the gradients are O(1), and one bf16 rounding step of the
-largest gradient entry when they are larger (the weights A and the logit
-gradients dZ enter the matrix cores rounded to bf16, so every gradient entry
-carries a relative error of that order whatever its size).
+Tolerance on each of dq, dk, dv (helpers.check_grad): the flat 2e-2 max abs error of
+the forward wherever the tensor's largest entry is at most 5.12; beyond that, max abs
+error / max|ref| <= 2^-8, one bf16 rounding step of the largest entry (the weights A and
+the logit gradients dZ enter the matrix cores rounded to bf16, so every gradient entry
+carries a relative error of that order whatever its size).  The ratio is printed for
+every tensor.
 """
 import numpy as np
 import pytest
 import torch
 
-from helpers import BF16_TOL, dev, max_abs, nan_bytes, to64
+from helpers import check_grad, dev, nan_bytes, to64
 
 pytestmark = pytest.mark.gpu
 
@@ -40,20 +41,10 @@ def gpu_grads(sb, q, k, v, g):
     return to64(dq), to64(dk), to64(dv)
 
 
-def grad_tol(ref):
-    return max(BF16_TOL, 2.0 ** -8 * float(np.abs(ref).max()))
-
-
 def check(sb, oracle, q, k, v, g):
     dq, dk, dv = gpu_grads(sb, q, k, v, g)
     rq, rk, rv = oracle.bwd(to64(q), to64(k), to64(v), to64(g))
-    errs = {}
-    for name, a, r in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
-        assert np.all(np.isfinite(a)), name
-        errs[name] = max_abs(a, r)
-        print(f"{name}: err {errs[name]:.3e} max|ref| {np.abs(r).max():.3e} tol {grad_tol(r):.3e}")
-        assert errs[name] <= grad_tol(r), f"{name}: max abs err {errs[name]} (max |ref| {np.abs(r).max()})"
-    return errs
+    return {name: check_grad(name, a, r) for name, a, r in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv))}
 
 
 @pytest.mark.parametrize("T", [1, 2, 32, 33, 64, 65, 100, 129, 257, 300])
@@ -139,9 +130,7 @@ def test_workload_4_sampled_heads(sb, oracle, gen):
     for b, h in gen.slice_picks(w, 4):
         rq, rk, rv = oracle.bwd(to64(q[b, h]), to64(k[b, h]), to64(v[b, h]), to64(g[b, h]))
         for name, a, r in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
-            err = max_abs(to64(a[b, h]), r)
-            print(f"{name}[{b},{h}]: err {err:.3e} max|ref| {np.abs(r).max():.3e}")
-            assert err <= grad_tol(r), f"{name}[{b},{h}]: {err} (max |ref| {np.abs(r).max()})"
+            check_grad(f"{name}[{b},{h}]", to64(a[b, h]), r)
     assert torch.isfinite(dq).all() and torch.isfinite(dk).all() and torch.isfinite(dv).all()
 
 
@@ -161,9 +150,7 @@ def test_headline_shape_step_sampled_heads(sb, oracle, gen):
     for b, h in picks:
         rq, rk, rv = oracle.bwd(to64(q[b, h]), to64(k[b, h]), to64(v[b, h]), to64(g[b, h]))
         for name, a, r in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
-            err = max_abs(to64(a[b, h]), r)
-            print(f"{name}[{b},{h}]: err {err:.3e} max|ref| {np.abs(r).max():.3e}")
-            assert err <= grad_tol(r), f"{name}[{b},{h}]: {err} (max |ref| {np.abs(r).max()})"
+            check_grad(f"{name}[{b},{h}]", to64(a[b, h]), r)
     assert torch.isfinite(dq).all() and torch.isfinite(dk).all() and torch.isfinite(dv).all()
 
 
@@ -180,9 +167,7 @@ def test_long_context_backward_one_head(sb, oracle, gen):
     for h in (1, 6):                                   # a plain and a sharp head
         rq, rk, rv = oracle.bwd(to64(q[0, h]), to64(k[0, h]), to64(v[0, h]), to64(g[0, h]))
         for name, a, r in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
-            err = max_abs(to64(a[0, h]), r)
-            print(f"{name}[0,{h}]: err {err:.3e} max|ref| {np.abs(r).max():.3e}")
-            assert err <= grad_tol(r), f"{name}[0,{h}]: {err} (max |ref| {np.abs(r).max()})"
+            check_grad(f"{name}[0,{h}]", to64(a[0, h]), r)
 
 
 @pytest.mark.parametrize("d", [64, 128])
@@ -200,9 +185,7 @@ def test_bwd_log_domain_redo_of_every_block(sb, oracle, gen, d):
     for b, h in ((0, 0), (2, 7), (3, 15)):
         rq, rk, rv = oracle.bwd(to64(q[b, h]), to64(k[b, h]), to64(v[b, h]), to64(g[b, h]))
         for name, a, r in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
-            err = max_abs(to64(a[b, h]), r)
-            print(f"{name}[{b},{h}]: err {err:.3e} max|ref| {np.abs(r).max():.3e}")
-            assert err <= grad_tol(r), f"{name}[{b},{h}]: {err} (max |ref| {np.abs(r).max()})"
+            check_grad(f"{name}[{b},{h}]", to64(a[b, h]), r)
 
 
 def test_bwd_split_passes_equal_the_whole(sb, gen):

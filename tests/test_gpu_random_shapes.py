@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import BF16_TOL, check_m, dev, max_abs, nan_bytes, to64
+from helpers import check_grad, fwd_bound, BF16_TOL, check_m, dev, max_abs, nan_bytes, to64
 
 pytestmark = pytest.mark.gpu
 
@@ -67,14 +67,10 @@ def test_random_shape_forward_and_backward(sb, oracle, gen, case):
     ref, rem = oracle.fwd(to64(q), to64(k), to64(v))
     og = to64(o)
     assert np.all(np.isfinite(og))
-    bound = np.maximum(BF16_TOL, 2.0 ** -8 * np.abs(ref) + 2.0 ** -9 * float(np.abs(to64(v)).max()))
-    excess = np.abs(og - ref) - bound
+    excess = np.abs(og - ref) - fwd_bound(ref, to64(v))
     assert excess.max() <= 0.0, f"forward: error exceeds the bound by {excess.max()}"
     check_m(to64(m), rem)
 
     refs = oracle.bwd(to64(q), to64(k), to64(v), to64(g))
     for name, got, r in zip(("dq", "dk", "dv"), (dq, dk, dv), refs):
-        got = to64(got)
-        assert np.all(np.isfinite(got)), name
-        tol = max(BF16_TOL, 2.0 ** -8 * float(np.abs(r).max()))
-        assert max_abs(got, r) <= tol, f"{name}: {max_abs(got, r)} > {tol}"
+        check_grad(name, to64(got), r)
