@@ -129,14 +129,16 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* Kg = k + kvrow0 * D;
     const uint16_t* Vg = v + kvrow0 * D;
 
-    // ---- per-lane LDS byte offsets inside a 32-row subtile
-    int aoff[D / 16];                       // K rows as A operand: row perm_row(n), chunk 2s + hh
+    // ---- per-lane LDS byte addresses inside the first 32-row subtile of the first staging
+    // buffer; every other subtile, matrix and buffer is a compile-time constant further on
+    const uint32_t smem0 = lds_offset(smem);
+    uint32_t aoff[D / 16];                  // K rows as A operand: row perm_row(n), chunk 2s + hh
     {
         const int key_l = perm_row(n);
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s) aoff[s] = tile_off_perm<D>(key_l, 2 * s + hh);
+        for (int s = 0; s < D / 16; ++s) aoff[s] = smem0 + tile_off_perm<D>(key_l, 2 * s + hh);
     }
-    int vtr[D / 32][2];                     // V through the transposing load: rows 16hh + li/4 (+4t, +8s)
+    uint32_t vtr[D / 32][2];                // V through the transposing load: rows 16hh + li/4 (+4t, +8s)
     {
         const int row_l = 16 * (gg >> 1) + (li >> 2);
         const int cl = 2 * (gg & 1) + ((li & 3) >> 1);
@@ -144,7 +146,7 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         for (int b = 0; b < D / 32; ++b)
 #pragma unroll
             for (int t = 0; t < 2; ++t)
-                vtr[b][t] = tile_off_perm<D>(row_l + 4 * t, 4 * b + cl) + 8 * (li & 1);
+                vtr[b][t] = smem0 + tile_off_perm<D>(row_l + 4 * t, 4 * b + cl) + 8 * (li & 1);
     }
 
     // ---- direct global -> LDS staging of one 64-row tile of K and of V.
@@ -192,17 +194,20 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 
     // operand fetches from LDS, kept apart from the MFMAs that use them so that they
     // can be issued a phase ahead
-    auto k_fetch = [&](const char* kslot, u32x4 (&kop)[D / 16]) __attribute__((always_inline)) {
+    // kslot / vslot: byte offset of the subtile's K / V rows from the start of the LDS tile
+    // array; a compile-time constant in the unrolled sweep (it then rides in the instruction's
+    // offset field), a runtime value in the diagonal band
+    auto k_fetch = [&](uint32_t kslot, u32x4 (&kop)[D / 16]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s) kop[s] = *reinterpret_cast<const u32x4*>(kslot + aoff[s]);
+        for (int s = 0; s < D / 16; ++s) kop[s] = lds_load16(aoff[s] + kslot);
     };
-    auto v_fetch = [&](const char* vslot, bf16x8 (&vop)[D / 16]) __attribute__((always_inline)) {
+    auto v_fetch = [&](uint32_t vslot, bf16x8 (&vop)[D / 16]) __attribute__((always_inline)) {
 #pragma unroll
         for (int b = 0; b < D / 32; ++b)
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const char* pp = vslot + (8 * s) * C::ROW;
-                vop[2 * b + s] = tr_pair(pp + vtr[b][0], pp + vtr[b][1]);
+                const uint32_t pp = vslot + (8 * s) * C::ROW;
+                vop[2 * b + s] = tr_pair_at(vtr[b][0] + pp, vtr[b][1] + pp);
             }
     };
     // S^T = K Q^T
@@ -279,9 +284,9 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     };
 
     // one 32-key subtile, start to end (tiles that touch the diagonal band)
-    auto subtile = [&](auto mask_c, const char* stage_ptr, int sub) __attribute__((always_inline)) {
-        const char* kslot = stage_ptr + sub * 32 * C::ROW;
-        const char* vslot = stage_ptr + C::KT_BYTES + sub * 32 * C::ROW;
+    auto subtile = [&](auto mask_c, uint32_t stage_off, int sub) __attribute__((always_inline)) {
+        const uint32_t kslot = stage_off + sub * 32 * C::ROW;
+        const uint32_t vslot = stage_off + C::KT_BYTES + sub * 32 * C::ROW;
         u32x4 kop[D / 16];
         bf16x8 vop[D / 16];
         k_fetch(kslot, kop);
@@ -293,7 +298,7 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     };
     // a full tile, upper subtile first, written so that the operand fetches of a phase
     // can be issued during the phase before it
-    auto hot_tile = [&](const char* sp) __attribute__((always_inline)) {
+    auto hot_tile = [&](uint32_t sp) __attribute__((always_inline)) {
         u32x4 kop[D / 16];
         bf16x8 vop[D / 16];
         bf16x8 p[2];
@@ -350,11 +355,11 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             // or the waves of a workgroup could disagree about leaving the loop.
             if constexpr (HALT) barrier_lds(); else barrier_nofence();
             stage_tile(max(ntile - 2 - it, 0), (it + 1) % NS);
-            return (const char*)(smem + (it % NS) * C::STAGE);
+            return (uint32_t)((it % NS) * C::STAGE);
         };
         int it = 0;
         for (; it < ndiag; ++it) {                           // tiles that touch the diagonal band
-            const char* sp = begin_iter(it);
+            const uint32_t sp = begin_iter(it);
             const int jt = ntile - 1 - it;
             if (wave_live) {
 #pragma unroll
@@ -368,8 +373,21 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         if constexpr (HALT) {
             if (lane == 0) { s_halt[0][wave] = 0; s_halt[1][wave] = 0; }   // read only after later barriers
         }
+        if constexpr (!HALT) {
+            // Tiles fully visible to every row, two per trip with the staging buffer a
+            // compile-time constant, so that every LDS read of the sweep is a precomputed
+            // register plus an immediate: no address arithmetic in the loop.
+            static_assert(NS == 2, "the unrolled sweep alternates two buffers");
+            if ((it & 1) && it < ntile) { hot_tile(begin_iter(it)); ++it; }
+            for (; it + 1 < ntile; it += 2) {
+                begin_iter(it);
+                hot_tile(0u);
+                begin_iter(it + 1);
+                hot_tile((uint32_t)C::STAGE);
+            }
+        }
         for (; it < ntile; ++it) {                           // tiles fully visible to every row
-            const char* sp = begin_iter(it);
+            const uint32_t sp = begin_iter(it);
             if constexpr (HALT) {
                 // flags of the previous iteration, written before the barrier just passed; all
                 // waves read the same four words, so they leave the loop together
