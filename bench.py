@@ -354,6 +354,11 @@ def main():
         fwd()
     fwd_mhz = sb.sb_diag_fwd_clock(qd, kd, vd, o, m)
 
+    # the other way to take Algorithm 1's in-tile cumulative sum: triangular-matrix MFMA in the
+    # log domain (measurement variant, same outputs to the same tolerance)
+    ms_tri = event_time_ms(lambda: sb.sb_diag_fwd_tri(qd, kd, vd, o, m), args.kernel_iters)
+    ms_fwd_again = event_time_ms(fwd, args.kernel_iters)
+
     # context: the vendor GEMM (hipBLASLt through torch.mm) on a large square bf16 problem
     n_g = 8192
     ga = torch.randn(n_g, n_g, device="cuda", dtype=torch.bfloat16)
@@ -406,6 +411,11 @@ def main():
                                 "streaming_read_gbs": stream_gbs,
                                 "frac_streaming_read": dec_bytes / (ms_dec * 1e-3) / 1e9 / stream_gbs}},
         "fwd_shader_clock_mhz": fwd_mhz,
+        "cumsum_variants": {"in_lane_chain_ms": ms_fwd_again, "triangular_mfma_ms": ms_tri,
+                            "what": "training forward at the headline workload with the in-tile reverse "
+                                    "cumulative sum as the in-lane linear-domain chain (product path) and "
+                                    "as a triangular-ones MFMA in the log domain (sb_diag_fwd_tri), "
+                                    "timed back to back"},
         "gemm_reference": {"tflops": gemm_tf, "frac_bf16_peak": gemm_tf / PEAK_BF16_TFLOPS, "ms": ms_gemm,
                            "what": "torch.mm (hipBLASLt), bf16, 8192^3, N(0,1) data: the vendor's dense "
                                    "contraction on this chip, for context"},

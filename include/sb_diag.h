@@ -46,6 +46,19 @@ int sb_diag_stream_read(const void* data, size_t bytes, unsigned int* sink, void
 int sb_diag_fwd_clock(const void* q, const void* k, const void* v, void* o, float* m,
                       int B, int H, int T, int d, unsigned long long* clocks, void* stream);
 
+/*
+ * The training forward (sb_attn_fwd_train: same arguments, same outputs to the same tolerance)
+ * with the other of the two ways the in-tile reverse cumulative sum of Algorithm 1 can be
+ * taken on this chip: on the matrix pipe, as a product with a triangular matrix of ones, in
+ * the log form of Eq. 2 (softplus per element, the sum by MFMA with the summands split into
+ * two bf16 parts, one more exponential per weight).  The product path uses an in-lane chain
+ * instead; this entry point exists so that the choice is a measured one.  d = 128 only
+ * (SB_ERR_UNSUPPORTED otherwise).  Logits beyond the range of the base-2 softplus are fine
+ * (it is overflow-proof).
+ */
+int sb_diag_fwd_tri(const void* q, const void* k, const void* v, void* o, float* m,
+                    int B, int H, int T, int d, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ EXPORTS = (
     "sb_attn_fwd_rb", "sb_attn_bwd_rb", "sb_attn_fwd_gqa", "sb_attn_bwd_gqa",
     "sb_attn_varlen_fwd", "sb_attn_varlen_bwd_workspace_bytes", "sb_attn_varlen_bwd",
     "sb_attn_decode_workspace_bytes", "sb_attn_decode", "sb_attn_decode_static",
-    "sb_diag_mfma_rate", "sb_diag_stream_read", "sb_diag_fwd_clock",
+    "sb_diag_mfma_rate", "sb_diag_stream_read", "sb_diag_fwd_clock", "sb_diag_fwd_tri",
     "sb_status_string", "sb_version",
 )
 
@@ -87,6 +87,8 @@ def load(build_if_missing: bool = True):
     lib.sb_diag_stream_read.restype = ci
     lib.sb_diag_fwd_clock.argtypes = [vp, vp, vp, vp, fp, ci, ci, ci, ci, vp, vp]
     lib.sb_diag_fwd_clock.restype = ci
+    lib.sb_diag_fwd_tri.argtypes = [vp, vp, vp, vp, fp, ci, ci, ci, ci, vp]
+    lib.sb_diag_fwd_tri.restype = ci
     lib.sb_status_string.argtypes = [ci]
     lib.sb_status_string.restype = ctypes.c_char_p
     lib.sb_version.argtypes = []
@@ -486,3 +488,17 @@ def sb_diag_fwd_clock(q, k, v, o, m, stream=None):
     c = clocks.cpu().tolist()
     ref = c[3] - c[1]
     return (c[2] - c[0]) / (ref / 100e6) / 1e6 if ref > 0 else float("nan")
+
+
+def sb_diag_fwd_tri(q, k, v, o=None, m=None, stream=None):
+    """Training forward with the in-tile cumulative sum taken by triangular MFMA (d = 128)."""
+    B, H, T, d = _dims(q)
+    if o is None:
+        o = torch.empty_like(q)
+    if m is None:
+        m = torch.empty((B, H, T), dtype=torch.float32, device=q.device)
+    rc = load().sb_diag_fwd_tri(_ptr(q, torch.bfloat16, None, "q"), _ptr(k, torch.bfloat16, q.shape, "k"),
+                                _ptr(v, torch.bfloat16, q.shape, "v"), _ptr(o, torch.bfloat16, q.shape, "o"),
+                                _ptr(m, torch.float32, (B, H, T), "m"), B, H, T, d, _stream(stream))
+    _check(rc, "sb_diag_fwd_tri")
+    return o, m

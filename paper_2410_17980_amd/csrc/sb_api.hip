@@ -309,6 +309,19 @@ int sb_diag_fwd_clock(const void* q, const void* k, const void* v, void* o, floa
     return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
 }
 
+int sb_diag_fwd_tri(const void* q, const void* k, const void* v, void* o, float* m,
+                    int B, int H, int T, int d, void* stream)
+{
+    if (!q || !k || !v || !o || !m) return SB_ERR_NULL;
+    if (int rc = check_shape(B, H, T, d)) return rc;
+    if (d != 128) return SB_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(m)) return SB_ERR_ALIGN;
+    hipError_t e = sb::launch_fwd_bf16_tri(static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k),
+                                           static_cast<const uint16_t*>(v), static_cast<uint16_t*>(o), m,
+                                           B, H, T, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH;
+}
+
 const char* sb_status_string(int status)
 {
     switch (status) {

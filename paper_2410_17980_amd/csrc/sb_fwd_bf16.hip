@@ -67,7 +67,10 @@ template <bool B> using bc = std::integral_constant<bool, B>;
 // sequence s occupies rows cu[s] .. cu[s+1]-1, BH counts (sequence, head) pairs and T_arg,
 // nqb_arg describe the longest sequence (they size the grid); a workgroup whose pair of
 // blocks lies beyond its own sequence's end returns at once.
-template <int D, bool WRITE_M, bool HALT, bool RB, bool VL>
+// TRI: measurement variant of the element-wise path.  The in-tile reverse cumulative sum of
+// Algorithm 1 is taken on the matrix pipe, as a product with a triangular matrix of ones,
+// instead of the in-lane chain (see ew_tri()); everything else is the same kernel.
+template <int D, bool WRITE_M, bool HALT, bool RB, bool VL, bool TRI = false>
 __global__ void __launch_bounds__(64 * NW, D == 128 ? 2 : (D == 64 ? 3 : 4))
 fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                 const uint16_t* __restrict__ v, const uint16_t* __restrict__ rb,
@@ -80,6 +83,7 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     static_assert(!(HALT && WRITE_M), "a halted sweep does not know m");
     __shared__ __attribute__((aligned(1024))) char smem[NS * C::STAGE];
     __shared__ int s_halt[2][NW];                       // per iteration parity and wave: all rows exhausted
+    __shared__ __attribute__((aligned(16))) char s_tri[TRI ? 2 * 64 * 16 : 16];   // triangular operand, per lane
 
     // workgroup -> (head, pair of query blocks).  Consecutive workgroup ids go round
     // the 8 XCDs, so every XCD gets its own heads and K/V of a head stay in one L2.
@@ -124,6 +128,21 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const int n = lane & 31;          // query column inside the wave
     const int hh = lane >> 5;         // half-wave: keys 16*hh .. 16*hh+15 of a subtile
     const int gg = lane >> 4, li = lane & 15;
+    if constexpr (TRI) {
+        // A operand of C^T = U L^T, U[key][key'] = 1 for key' >= key (keys of one 32-key subtile).
+        // MFMA row rho stands for key perm_row(rho) (the accumulator layout of the logits), and
+        // K-dim element 8h + e of MFMA s stands for key 16h + 8s + e (the order in which a lane
+        // holds its 16 values).  Every wave writes the same words: benign.
+        const int key_out = perm_row(n);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            bf16x8 u;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) u[e] = (16 * hh + 8 * s + e >= key_out) ? (__bf16)1.0f : (__bf16)0.0f;
+            *reinterpret_cast<bf16x8*>(s_tri + (s * 64 + lane) * 16) = u;
+        }
+        __syncthreads();
+    }
 
     const uint16_t* Qg = q + row0 * D;
     const uint16_t* Kg = k + kvrow0 * D;
@@ -283,6 +302,39 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         }
     };
 
+    // The same step in the log form of Eq. 2 with Algorithm 1's in-tile cumulative sum on the
+    // matrix pipe (unmasked subtiles only).  L = sp2(x) per element (two transcendentals); the
+    // inclusive sums over the keys from a lane's own key to the subtile's last key, both
+    // half-waves at once, are C^T = U L^T with L split into a bf16 head and a bf16 remainder
+    // (one bf16 alone would leave 2^-9 of up to 32 summands in the exponent): four MFMAs.  The
+    // weight is 2^(x - C - carry), a third transcendental.
+    auto ew_tri = [&](const f32x16& sin, bf16x8 (&pout)[2]) __attribute__((always_inline)) {
+        float y[16];
+        bf16x8 lh[2], ll[2];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            y[r] = sin[r] * c2;
+            const float L = sp2(y[r]);
+            const __bf16 h = (__bf16)L;
+            lh[r >> 3][r & 7] = h;
+            ll[r >> 3][r & 7] = (__bf16)(L - (float)h);
+        }
+        const bf16x8 u0 = *reinterpret_cast<const bf16x8*>(s_tri + lane * 16);
+        const bf16x8 u1 = *reinterpret_cast<const bf16x8*>(s_tri + (64 + lane) * 16);
+        f32x16 c;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) c[r] = 0.0f;
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u0, lh[0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u1, lh[1], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u0, ll[0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u1, ll[1], c, 0, 0, 0);
+        float t_lo, t_hi;
+        both_halves(c[0], t_lo, t_hi);                 // key 0's sum (lanes 0-31) is the subtile's total
+#pragma unroll
+        for (int r = 0; r < 16; ++r) pout[r >> 3][r & 7] = (__bf16)fast_exp2((y[r] - c[r]) - a);
+        a += t_lo;
+    };
+
     // one 32-key subtile, start to end (tiles that touch the diagonal band)
     auto subtile = [&](auto mask_c, uint32_t stage_off, int sub) __attribute__((always_inline)) {
         const uint32_t kslot = stage_off + sub * 32 * C::ROW;
@@ -305,12 +357,12 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         k_fetch(sp + 32 * C::ROW, kop);
         f32x16 s = s_mfma(kop);
         v_fetch(sp + C::KT_BYTES + 32 * C::ROW, vop);
-        ew(bc<false>{}, s, p);
+        if constexpr (TRI) ew_tri(s, p); else ew(bc<false>{}, s, p);
         k_fetch(sp, kop);
         pv_mfma(vop, p);
         s = s_mfma(kop);
         v_fetch(sp + C::KT_BYTES, vop);
-        ew(bc<false>{}, s, p);
+        if constexpr (TRI) ew_tri(s, p); else ew(bc<false>{}, s, p);
         pv_mfma(vop, p);
     };
 
@@ -451,7 +503,7 @@ fwd_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     }
 }
 
-template <int D, bool WRITE_M, bool HALT, bool RB, bool VL = false>
+template <int D, bool WRITE_M, bool HALT, bool RB, bool VL = false, bool TRI = false>
 hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,
                       uint16_t* o, float* m, int BH, int H, int G, int T, float halt_carry,
                       unsigned long long* tile_counts, hipStream_t stream,
@@ -461,7 +513,7 @@ hipError_t launch_one(const uint16_t* q, const uint16_t* k, const uint16_t* v, c
     const long blocks = 8L * ((BH + 7) / 8) * ((nqb + 1) / 2);
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
     if (blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL((fwd_bf16_kernel<D, WRITE_M, HALT, RB, VL>), dim3((unsigned)blocks), dim3(64 * NW), 0, stream,
+    hipLaunchKernelGGL((fwd_bf16_kernel<D, WRITE_M, HALT, RB, VL, TRI>), dim3((unsigned)blocks), dim3(64 * NW), 0, stream,
                        q, k, v, rb, o, m, T, BH, H, G, nqb, halt_carry, tile_counts, cu, Ttot);
     return hipGetLastError();
 }
@@ -486,6 +538,12 @@ hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t*
     if (rb) return m ? SB_FWD(128, true, true) : SB_FWD(128, false, true);
     return m ? SB_FWD(128, true, false) : SB_FWD(128, false, false);
 #undef SB_FWD
+}
+
+hipError_t launch_fwd_bf16_tri(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o, float* m,
+                               int B, int H, int T, hipStream_t stream)
+{
+    return launch_one<128, true, false, false, false, true>(q, k, v, nullptr, o, m, B * H, H, 1, T, 0.0f, nullptr, stream);
 }
 
 hipError_t launch_fwd_bf16_varlen(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* rb,

@@ -20,6 +20,10 @@ hipError_t launch_fwd_bf16(const uint16_t* q, const uint16_t* k, const uint16_t*
                            uint16_t* o, float* m, int B, int H, int Hkv, int T, int d, hipStream_t stream,
                            unsigned long long* clocks = nullptr);
 
+// measurement variant of the d = 128 training forward: in-tile cumulative sum by triangular MFMA
+hipError_t launch_fwd_bf16_tri(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o, float* m,
+                               int B, int H, int T, hipStream_t stream);
+
 // forward that stops sweeping a query block once every row has less than eps of its stick left
 hipError_t launch_fwd_bf16_halt(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* o,
                                 float eps, unsigned long long* tile_counts,

@@ -246,3 +246,24 @@ def test_halt_rejects_bad_eps(sb, gen):
     for eps in (0.0, 1.0, -1.0, float("nan")):
         with pytest.raises(sb.SbAttnError):
             sb.sb_attn_fwd_halt(q, k, v, eps)
+
+
+@pytest.mark.parametrize("kind", ["gaussian", "long_range", "sharp"])
+def test_triangular_mfma_cumsum_variant(sb, oracle, gen, kind):
+    """The measurement variant of the forward (in-tile cumulative sum as a product with a
+    triangular matrix of ones on the matrix pipe, log form of Eq. 2) meets the same bound as the
+    product path; T spans the diagonal band and many unmasked tiles."""
+    if kind == "gaussian":
+        q, k, v = gen.gaussian(2, 4, 1000, 128, seed=41, dtype="bf16", sharp_half=True)
+    elif kind == "long_range":
+        q, k, v = gen.biased_gaussian(1, 2, 1300, 128, seed=42, shift=-6.0)
+    else:
+        q, k, v = gen.scaled_gaussian(1, 2, 700, 128, seed=43, gain=30.0)
+    qd, kd, vd = dev(q, k, v)
+    o, m = sb.sb_diag_fwd_tri(qd, kd, vd)
+    torch.cuda.synchronize()
+    ref, rem = oracle.fwd(to64(q), to64(k), to64(v))
+    err = max_abs(to64(o), ref)
+    print(f"triangular-MFMA variant, {kind}: max abs err {err:.3e}")
+    assert err <= BF16_TOL
+    check_m(to64(m), rem)
