@@ -226,6 +226,40 @@ def config_entries(sb, inputs, iters, headline):
     return out
 
 
+def run_one_config(sb, inputs, n, iters, calibrate_copy=False):
+    """One stated workload on its own (training forward, plus the backward for the backward
+    workload), launched `iters` times: the command a rocprofv3 run of that shape wraps."""
+    import torch
+    w = inputs.WORKLOADS[n - 1]
+    B, H, T, d = w.B, w.H, w.T, w.d
+    ts = [t.cuda() for t in inputs.workload_tensors(w)]
+    q, k, v = ts[:3]
+    if calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.bitwise_or(src, 0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+    o = torch.empty_like(q)
+    if w.dtype == "f32":
+        fn = lambda: sb.sb_attn_fwd_f32(q, k, v, o)
+    else:
+        m = torch.empty((B, H, T), dtype=torch.float32, device="cuda")
+        if w.direction == "fwd":
+            fn = lambda: sb.sb_attn_fwd_train(q, k, v, o, m)
+        else:
+            dq = torch.empty((B, H, T, d), dtype=torch.float32, device="cuda")
+            dk, dv = torch.empty_like(dq), torch.empty_like(dq)
+            ws = torch.empty(sb.sb_attn_bwd_workspace_bytes(B, H, T, d), dtype=torch.uint8, device="cuda")
+
+            def fn():
+                sb.sb_attn_fwd_train(q, k, v, o, m)
+                sb.sb_attn_bwd(q, k, v, m, ts[3], dq, dk, dv, ws)
+    ms = event_time_ms(fn, iters)
+    return {"config": n, "workload": w.name, "launches": iters, "ms": ms}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -236,6 +270,9 @@ def main():
     ap.add_argument("--passes", choices=["fwd", "fwd+bwd"], default=DEFAULT_PASSES,
                     help="what one step runs")
     ap.add_argument("--no-configs", action="store_true", help="skip the per-workload `configs` array")
+    ap.add_argument("--only-config", type=int, default=0, metavar="N",
+                    help="profiling aid: run only stated workload N (1-5) --kernel-iters times, print its timing "
+                         "and exit (what a rocprofv3 run of one of the other shapes wraps)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB element-wise copy kernel (3 times): the known traffic the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by")
@@ -252,6 +289,10 @@ def main():
         sys.exit("bench.py: no GPU visible")
     sb.load(build_if_missing=True)
     torch.cuda.set_device(0)
+
+    if args.only_config:
+        print(json.dumps(run_one_config(sb, inputs, args.only_config, args.kernel_iters, args.calibrate_copy)))
+        return
 
     w = inputs.WORKLOADS[2]
     B, H, T, d = w.B, w.H, w.T, w.d

@@ -53,6 +53,15 @@ constexpr int TROW = 80;     // scratch row: 32 bf16 + pad (rows stay 16 B align
 
 template <bool B> using bc = std::integral_constant<bool, B>;
 
+#ifndef SB_SIGMA_DQ
+#define SB_SIGMA_DQ 2
+#endif
+#ifndef SB_SIGMA_DKV
+#define SB_SIGMA_DKV 2
+#endif
+constexpr int SIGMA_DQ = SB_SIGMA_DQ;     // how each pass forms sigma (see subtile_stage1)
+constexpr int SIGMA_DKV = SB_SIGMA_DKV;
+
 // ------------------------------------------------------------------ element-wise core
 // One 32x32 subtile in the lane layout (query n; keys 16hh + r).
 struct SubtileOut {
@@ -129,9 +138,13 @@ struct Chain {
     float W;         // end of the chain
 };
 
-// VIA_CHAIN: sigma = e / (1 + e) taken as t_r / W_{r+1} (one add fewer, but serial with the
-// chain): faster in the key-stationary kernel, slower in the query-stationary one (measured)
-template <bool MASK, bool VIA_CHAIN = false>
+// How sigma = e / (1 + e) is formed (SIGMA):
+//   0  e * rcp(1 + e): independent of the chain, an add and a reciprocal per element;
+//   1  t_r * rcp(W_{r+1}): one add fewer, but the reciprocal waits for the chain;
+//   2  t_r * (1 / W_{r+1}) with the 16 reciprocals from ONE reciprocal and a second chain run
+//      backwards, 1/W_r = 1/W_{r+1} * (1 + e_r): a fused multiply-add per element in place of
+//      the reciprocal (a transcendental, about twice the cost of a plain instruction here).
+template <bool MASK, int SIGMA = 0>
 __device__ __forceinline__ bool subtile_stage1(Chain& ch, const f32x16& sacc, float c2, int n, int hh)
 {
     float W = 0x1p-60f;
@@ -141,9 +154,20 @@ __device__ __forceinline__ bool subtile_stage1(Chain& ch, const f32x16& sacc, fl
         if (MASK) e = (16 * hh + r < n) ? e : 0.0f;
         ch.t[r] = W * e;
         W += ch.t[r];
-        ch.be[r] = VIA_CHAIN ? ch.t[r] * __builtin_amdgcn_rcpf(W) : e * __builtin_amdgcn_rcpf(1.0f + e);
+        if (SIGMA == 0) ch.be[r] = e * __builtin_amdgcn_rcpf(1.0f + e);
+        else if (SIGMA == 1) ch.be[r] = ch.t[r] * __builtin_amdgcn_rcpf(W);
+        else ch.be[r] = e;                                 // kept for the backward chain below
     }
     ch.W = W;
+    if (SIGMA == 2) {
+        float inv = __builtin_amdgcn_rcpf(W);              // 1 / W_16; 0 where the chain overflowed
+#pragma unroll
+        for (int r = 15; r >= 0; --r) {
+            const float e = ch.be[r];
+            ch.be[r] = ch.t[r] * inv;                      // t_r / W_{r+1}
+            inv = __builtin_fmaf(inv, e, inv);             // 1 / W_r
+        }
+    }
     return W < 0x1p80f;                                    // false: this lane's chain left its range
 }
 
@@ -362,7 +386,7 @@ bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         } else {
             Chain ch;
             const f32x16 sacc = s_mfma();
-            dirty |= !subtile_stage1<MASK>(ch, sacc, c2, n, hh);
+            dirty |= !subtile_stage1<MASK, SIGMA_DQ>(ch, sacc, c2, n, hh);
             const f32x16 pacc = p_mfma();
             subtile_stage2<true, false>(so, ch, pacc, a2, bsum, hh);
         }
@@ -688,7 +712,7 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             subtile_math_log<false, MASK>(so, sacc, pacc, car, cbl, c2, n, hh);
         } else {
             Chain ch;
-            dirty |= !subtile_stage1<MASK, true>(ch, sacc, c2, n, hh);
+            dirty |= !subtile_stage1<MASK, SIGMA_DKV>(ch, sacc, c2, n, hh);
             subtile_stage2<false, true>(so, ch, pacc, car, cbl, hh);
         }
         bf16x8 at[2], zt[2];
@@ -980,7 +1004,7 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             subtile_math_log<false, MASK>(so, sacc, pacc, car, cbl, c2, n, hh);
         } else {
             Chain ch;
-            dirty |= !subtile_stage1<MASK, true>(ch, sacc, c2, n, hh);
+            dirty |= !subtile_stage1<MASK, SIGMA_DKV>(ch, sacc, c2, n, hh);
             subtile_stage2<false, true>(so, ch, pacc, car, cbl, hh);
         }
         const uint32_t w = sc + role * CK::W_BYTES + sw_off;
@@ -1032,7 +1056,7 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         __builtin_amdgcn_sched_barrier(0);
         // phase B: the chain of the logits (vector) beside dO.v and the back of subtile 0 (matrix)
         Chain ch;
-        dirty |= !subtile_stage1<false, true>(ch, sacc, c2, n, hh);
+        dirty |= !subtile_stage1<false, SIGMA_DKV>(ch, sacc, c2, n, hh);
 #pragma unroll
         for (int s = 0; s < D / 16; ++s)
             pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s], __builtin_bit_cast(bf16x8, gw[s]), pacc, 0, 0, 0);
