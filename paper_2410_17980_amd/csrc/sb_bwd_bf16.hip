@@ -49,7 +49,19 @@ constexpr int NW = 4;        // wavefronts per workgroup
 constexpr int BQ = 128;      // dq kernel: query rows per block
 constexpr int BKW = 128;     // dkv kernel: key rows per block (32 per wave)
 constexpr int TK = 64;       // rows per staged tile (keys in the dq kernel, queries in the dkv kernel)
-constexpr int TROW = 80;     // scratch row: 32 bf16 + pad (rows stay 16 B aligned)
+constexpr int SCR_MAT = 32 * 64;   // one 32x32 bf16 matrix of the A / dZ transposition scratch
+
+// Byte offset of 16-byte chunk c (0..3) of row `row` of a scratch matrix.  16-byte LDS writes
+// are taken eight lanes at a time (measured: 8 cycles per conflict-free ds_write_b128), so the
+// eight rows 8i .. 8i+7 that write the same chunk together must land in eight different 16-byte
+// slots of a 128-byte window: the chunk index is xor-ed with bits 1-2 of the row (rows 2j and
+// 2j+1 already differ by 64 bytes).  The transposing reads take four whole rows at a time and
+// do not care how a row's chunks are permuted.  Counters: no bank conflicts either way (the
+// same layout with bits 2-3 of the row costs 8 conflict cycles per write).
+__device__ __forceinline__ int scr_off(int row, int c)
+{
+    return row * 64 + ((c ^ ((row >> 1) & 3)) << 4);
+}
 
 template <bool B> using bc = std::integral_constant<bool, B>;
 
@@ -564,7 +576,7 @@ __device__ __forceinline__ bool kv_head(KvHead& kh, long bh, int pidx, int T_arg
 // ------------------------------------------------------------------ dK / dV kernel
 template <int D> struct DkvCfg {
     static constexpr int T_OFF = 2 * StageCfg<D>::STAGE;   // after the double buffer
-    static constexpr int T_WAVE = 2 * 32 * TROW;           // A and dZ scratch of one wave
+    static constexpr int T_WAVE = 2 * SCR_MAT;             // A and dZ scratch of one wave
     static constexpr int LDS_BYTES = T_OFF + NW * T_WAVE;
 };
 
@@ -620,9 +632,12 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     }
     int goff[C::NPW];
     stage_offsets<D, false>(goff, wave, lane);
-    char* const scr = smem + CK::T_OFF + wave * CK::T_WAVE;               // [2][32][TROW]
-    const int sw_off = n * TROW + 32 * hh;                                // scratch write: row = query n
-    const int st_off = (8 * (gg >> 1) + (li >> 2)) * TROW + (16 * (gg & 1) + 4 * (li & 3)) * 2;
+    char* const scr = smem + CK::T_OFF + wave * CK::T_WAVE;               // [A, dZ][32 rows of 64 B]
+    const int sw_off = scr_off(n, 2 * hh);                                // scratch write: row = query n; second chunk: ^ 16
+    int st_off[2];                                                        // transposing reads, rows 8h + li/4 (+ 4t)
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+        st_off[t] = scr_off(8 * (gg >> 1) + (li >> 2) + 4 * t, 2 * (gg & 1) + ((li & 3) >> 1)) + 8 * (li & 1);
 
     const float scale = 1.0f / sqrtf((float)D);
     const float c2 = SB_LOG2E * scale;
@@ -658,16 +673,16 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     auto transpose = [&](const SubtileOut& so, bf16x8 (&at)[2], bf16x8 (&zt)[2]) __attribute__((always_inline)) {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         *reinterpret_cast<bf16x8*>(scr + sw_off) = so.pa[0];
-        *reinterpret_cast<bf16x8*>(scr + sw_off + 16) = so.pa[1];
-        *reinterpret_cast<bf16x8*>(scr + 32 * TROW + sw_off) = so.pz[0];
-        *reinterpret_cast<bf16x8*>(scr + 32 * TROW + sw_off + 16) = so.pz[1];
+        *reinterpret_cast<bf16x8*>(scr + (sw_off ^ 16)) = so.pa[1];
+        *reinterpret_cast<bf16x8*>(scr + SCR_MAT + sw_off) = so.pz[0];
+        *reinterpret_cast<bf16x8*>(scr + SCR_MAT + (sw_off ^ 16)) = so.pz[1];
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-            const char* pa = scr + (16 * s2) * TROW + st_off;
-            const char* pz = pa + 32 * TROW;
-            at[s2] = tr_pair(pa, pa + 4 * TROW);
-            zt[s2] = tr_pair(pz, pz + 4 * TROW);
+            const char* pa = scr + (16 * s2) * 64;         // rows 16 s2 + ..: same swizzle as rows 0..15
+            const char* pz = pa + SCR_MAT;
+            at[s2] = tr_pair(pa + st_off[0], pa + st_off[1]);
+            zt[s2] = tr_pair(pz + st_off[0], pz + st_off[1]);
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     };
@@ -869,13 +884,6 @@ template <int D> struct Dkv3Cfg {
     static constexpr int LOADS = StageCfg<D>::TILE / 1024;
     static constexpr int NPW = (LOADS + NW2 - 1) / NW2;
 };
-
-// byte offset of 16-byte chunk c (0..3) of row `row` of a scratch matrix: 16 lanes writing the
-// same chunk of 16 consecutive rows, and 32 lanes reading four whole rows, each touch every bank once
-__device__ __forceinline__ int scr_off(int row, int c)
-{
-    return row * 64 + ((c ^ ((row >> 2) & 3)) << 4);
-}
 
 template <int D, bool SLOW, bool GQA, bool VL>
 __global__ void __launch_bounds__(NTHREADS2, 1)
