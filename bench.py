@@ -222,6 +222,17 @@ def config_entries(sb, inputs, iters, headline):
                   "ok": bool(e["max_abs_err"] <= e["tol"])})
         if w.dtype == "f32":
             e["note"] = "vector-ALU fp32 check path, latency-bound at this size: not a matrix-core rate"
+        if w.dtype == "bf16" and w.direction == "fwd" and d == 64:
+            # At d = 64 the element-wise path outweighs the matrix work of a subtile: per MFMA 14.3
+            # vector instructions, 2.25 of them transcendental (profiles/counters_fwd_B8_H16_T2048_d64.md).
+            # At the published vector rate (157.3 TFLOP/s fp32 = one 64-lane instruction per 2 clocks per
+            # SIMD, transcendentals a quarter of that) a 32x32 subtile (8 MFMAs = 256 matrix clocks) needs
+            # 8 * (12.05 * 2 + 2.25 * 8) = 337 vector clocks: the vector ALU is the binding roof.
+            alu_clk, pairs = 8 * ((14.3 - 2.25) * 2.0 + 2.25 * 8.0), 1024
+            alu_roof = 4.0 * d * pairs / alu_clk * 1024 * 2.4e9 / 1e12
+            e["alu_roof"] = {"bound": "alu", "peak": alu_roof, "unit": "TFLOP/s", "frac": tf / alu_roof,
+                             "what": "vector-ALU clocks of a 32x32 subtile at the published fp32 vector rate, "
+                                     "instruction counts from the rocprofv3 counters of this kernel"}
         out.append(e)
     return out
 
