@@ -1046,23 +1046,36 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
 
     // front of this wave's subtile (Q rows at qtile) and back of the tile before (buffer ptile,
     // scratch scp), unmasked and complete, written as one block so that the matrix
-    // instructions of one part can be issued between the vector instructions of the other
-    auto step = [&](uint32_t qtile, uint32_t sc, uint32_t ptile, uint32_t scp, float car, float cbl) __attribute__((always_inline)) {
+    // instructions of one part can be issued between the vector instructions of the other.
+    // xn, yn: Q and dO rows of the tile to stage meanwhile, spn: its LDS buffer.
+    // The wave's priority falls from part to part: of the two waves of a SIMD the one that is
+    // behind wins the arbitration, so they reach the barrier closer together.
+    auto step = [&](uint32_t qtile, uint32_t sc, uint32_t ptile, uint32_t scp, float car, float cbl,
+                    const uint16_t* xn, const uint16_t* yn, const char* spn) __attribute__((always_inline)) {
         const uint32_t qa = qtile + boff0;
-        // phase A: logits
+        // part A: logits
+        __builtin_amdgcn_s_setprio(3);
         u32x4 qw[D / 16], gw[D / 16];
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) qw[s] = lds_load16(qa ^ (s << 5));
         f32x16 sacc, pacc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; pacc[r] = 0.0f; }
+        // the staging loads go out between the matrix instructions
+        static_assert(CK::LOADS == 2 * NW2, "two staging loads per wave and matrix");
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s)
+        for (int s = 0; s < D / 16; ++s) {
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], __builtin_bit_cast(bf16x8, qw[s]), sacc, 0, 0, 0);
+            if (s == 0) dma16_to_lds_saddr(xn, goff[0], spn + wave * 1024);
+            if (s == 2) dma16_to_lds_saddr(yn, goff[0], spn + C::TILE + wave * 1024);
+            if (s == 4) dma16_to_lds_saddr(xn, goff[1], spn + (wave + NW2) * 1024);
+            if (s == 6) dma16_to_lds_saddr(yn, goff[1], spn + C::TILE + (wave + NW2) * 1024);
+        }
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) gw[s] = lds_load16((qa ^ (s << 5)) + C::TILE);
         __builtin_amdgcn_sched_barrier(0);
-        // phase B: the chain of the logits (vector) beside dO.v and the back of subtile 0 (matrix)
+        __builtin_amdgcn_s_setprio(2);
+        // part B: the chain of the logits (vector) beside dO.v and the back of subtile 0 (matrix)
         Chain ch;
         dirty |= !subtile_stage1<false, SIGMA_DKV>(ch, sacc, c2, n, hh);
 #pragma unroll
@@ -1070,7 +1083,8 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s], __builtin_bit_cast(bf16x8, gw[s]), pacc, 0, 0, 0);
         back(ptile, scp, 0);
         __builtin_amdgcn_sched_barrier(0);
-        // phase C: A, G, dZ (vector) beside the back of subtile 1 (matrix)
+        __builtin_amdgcn_s_setprio(1);
+        // part C: A, G, dZ (vector) beside the back of subtile 1 (matrix)
         SubtileOut so;
         subtile_stage2<false, true>(so, ch, pacc, car, cbl, hh);
         back(ptile, scp, 1);
@@ -1079,6 +1093,8 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         lds_store16(w ^ 16, so.pa[1]);
         lds_store16(w + CK::M_BYTES, so.pz[0]);
         lds_store16((w ^ 16) + CK::M_BYTES, so.pz[1]);
+        __builtin_amdgcn_s_setprio(0);
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     for (int part = 0; part < 2; ++part) {
@@ -1136,9 +1152,48 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             load_carries(jt0);
             stage(jt0, smem);
         }
-        int bcur = 0, bprev = 2, bnext = 1;                  // tile buffers of tiles it, it - 1, it + 1
-        for (int it = 0; it <= ntile; ++it) {
-            if (it > 0) { bprev = bcur; bcur = bnext; bnext = bcur == 2 ? 0 : bcur + 1; }
+        // steady state (the intervals hot_begin .. hot_end - 1): the strip is live, tile `it` is past
+        // the diagonal band and complete, and the next tile is complete or does not exist
+        const int nfull = max(T / TK - jt0, 0);
+        const int hot_begin = ndiag + 1;
+        const int hot_end = (SLOW || !live) ? 0 : (nfull == ntile ? ntile : nfull - 1);
+        int it = 0;
+        while (it <= ntile) {
+            if (it == hot_begin && it < hot_end) {
+                // LDS addresses of the tile buffers of tiles it, it - 1, it + 1 and of the scratch
+                // of tiles it, it - 1; they rotate, nothing is recomputed.  The tile staged in an
+                // interval is tile it + 1, or, after the last one, that tile once more (never read).
+                uint32_t a_cur = smem0 + (it % 3) * C::STAGE, a_prev = smem0 + ((it + 2) % 3) * C::STAGE;
+                uint32_t a_next = smem0 + ((it + 1) % 3) * C::STAGE;
+                uint32_t s_cur = scr + (it & 1) * CK::SCR_BUF, s_prev = scr + ((it + 1) & 1) * CK::SCR_BUF;
+                const int tn = min(it + 1, ntile - 1);
+                const uint16_t* xn = Qg + (long)(jt0 + tn) * TK * D;
+                const uint16_t* yn = Gg + (long)(jt0 + tn) * TK * D;
+                const float* cap = cag + (jt0 + tn) * TK + 32 * role + n;
+                const float* cbp = cbg + (jt0 + tn) * TK + 32 * role + n;
+                for (; it < hot_end; ++it) {
+                    dma_wait<0>();
+                    barrier_lds();
+                    const float car = cn0, cbl = cn1;
+                    cn0 = *cap;
+                    cn1 = *cbp;
+                    step(a_cur + role * 32 * C::ROW, s_cur, a_prev, s_prev, car, cbl, xn, yn, smem + (a_next - smem0));
+                    const int adv = it + 2 < ntile ? TK : 0;
+                    xn += adv * D;
+                    yn += adv * D;
+                    cap += adv;
+                    cbp += adv;
+                    const uint32_t t = a_prev;
+                    a_prev = a_cur;
+                    a_cur = a_next;
+                    a_next = t;
+                    const uint32_t u = s_prev;
+                    s_prev = s_cur;
+                    s_cur = u;
+                }
+                continue;
+            }
+            const int bcur = it % 3, bprev = (it + 2) % 3, bnext = (it + 1) % 3;   // buffers of tiles it, it - 1, it + 1
             dma_wait<0>();
             barrier_lds();        // tile `it` has landed, the scratch of tile it-1 is complete, tile it-2 is free
             const float car = cn0, cbl = cn1;
@@ -1151,28 +1206,23 @@ bwd_dkv_pair_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             const uint32_t sc = scr + (it & 1) * CK::SCR_BUF;
             const uint32_t spp = smem0 + bprev * C::STAGE;
             const uint32_t scp = scr + ((it + 1) & 1) * CK::SCR_BUF;
-            if (!SLOW && live && it > ndiag && it < ntile && jbase + TK <= T) {
-                // steady state: the front of this wave's subtile of tile `it` and the back of
-                // tile it - 1 as one stream of independent matrix and vector work
-                step(qt, sc, spp, scp, car, cbl);
-            } else {
-                const int j0 = jbase + 32 * role;
-                if (it < ntile && live && j0 < T) {
-                    if (it < ndiag) {
-                        if (j0 == k0) front(bc<true>{}, qt, sc, car, cbl);
-                        else if (j0 > k0) front(bc<false>{}, qt, sc, car, cbl);
-                    } else {
-                        front(bc<false>{}, qt, sc, car, cbl);
-                    }
-                }
-                if (it >= 1 && live) {
-#pragma unroll
-                    for (int u = 0; u < 2; ++u) {
-                        const int ju = jbase - TK + 32 * u;
-                        if (ju >= k0 && ju < T) back(spp, scp, u);
-                    }
+            const int j0 = jbase + 32 * role;
+            if (it < ntile && live && j0 < T) {
+                if (it < ndiag) {
+                    if (j0 == k0) front(bc<true>{}, qt, sc, car, cbl);
+                    else if (j0 > k0) front(bc<false>{}, qt, sc, car, cbl);
+                } else {
+                    front(bc<false>{}, qt, sc, car, cbl);
                 }
             }
+            if (it >= 1 && live) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int ju = jbase - TK + 32 * u;
+                    if (ju >= k0 && ju < T) back(spp, scp, u);
+                }
+            }
+            ++it;
         }
         }
 
