@@ -866,8 +866,13 @@ bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 // Price: the Q/dO tile of the interval before must stay in LDS (three tile buffers) and the
 // A/dZ scratch is double buffered; with compact scratch rows (64 B, xor-swizzled) that is
 // exactly the 160 KB of a CU at d = 128.  Two waves per SIMD.
+// The steady-state intervals run in a loop of their own in which LDS addresses rotate through
+// registers and global pointers advance by constants: with one barrier per interval all eight
+// waves do their loop bookkeeping at the same time, and a hundred dependent scalar instructions
+// there cost about 500 clocks per interval.
 // Measured against the predecessor of this kernel (front and back as two phases with a
-// barrier each, padded scratch rows): 1.35 -> 1.29 ms at B8 H16 T4096.  Also measured:
+// barrier each, padded scratch rows): 1.35 -> 1.29 ms at B8 H16 T4096, 1.20 with the
+// steady-state loop.  Also measured:
 // the two roles taking front and back in opposite order within an interval (so that one
 // wave of a SIMD is in its vector phase while the other is in its matrix phase) is slower,
 // 1.47 ms: the compiler then copies the accumulator (64 registers) on every switch.
