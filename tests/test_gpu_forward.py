@@ -267,3 +267,26 @@ def test_triangular_mfma_cumsum_variant(sb, oracle, gen, kind):
     print(f"triangular-MFMA variant, {kind}: max abs err {err:.3e}")
     assert err <= BF16_TOL
     check_m(to64(m), rem)
+
+
+def test_clock_sampling_forward_is_the_training_forward(sb, gen):
+    """The forward that samples the shader clock (measurement aid) writes what
+    sb_attn_fwd_train writes, bit for bit, and reports a plausible clock."""
+    q, k, v = gen.gaussian(2, 4, 1100, 128, seed=44, dtype="bf16", sharp_half=True)
+    qd, kd, vd = dev(q, k, v)
+    o, m = sb.sb_attn_fwd_train(qd, kd, vd)
+    o2, m2 = torch.full_like(o, 7.0), torch.full_like(m, 7.0)
+    mhz = sb.sb_diag_fwd_clock(qd, kd, vd, o2, m2)
+    torch.cuda.synchronize()
+    assert torch.equal(o.view(torch.int16), o2.view(torch.int16))
+    assert torch.equal(m.view(torch.int32), m2.view(torch.int32))
+    assert 300.0 < mhz < 3000.0
+
+
+def test_streaming_read_diagnostic_runs(sb):
+    """The read-only streaming kernel (the decode path's practical ceiling) reports a rate
+    between what a single HBM stack and the whole chip can deliver."""
+    x = torch.randn(1 << 26, device="cuda")          # 256 MiB
+    gbs = sb.sb_diag_stream_read(x, iters=5)
+    print(f"streaming read: {gbs:.0f} GB/s")
+    assert 500.0 < gbs < 8500.0
