@@ -54,6 +54,16 @@ def test_bwd_shapes(sb, oracle, gen, T, d):
     check(sb, oracle, q, k, v, g)
 
 
+@pytest.mark.parametrize("T", [319, 320, 321, 383, 384, 385, 447, 448, 449, 511, 512, 513, 577, 640, 705])
+def test_bwd_steady_state_loop_boundaries(sb, oracle, gen, T):
+    """d = 128: lengths around the points where a key block's sweep gains its first steady-state
+    interval, where the last tile is complete, ragged by one row, or short by one row, and where
+    the tile after the steady state is the ragged one (the key-stationary pass stages that tile
+    from inside the steady-state loop only when it is complete)."""
+    q, k, v, g = gen.gaussian(1, 2, T, 128, seed=900 + T, dtype="bf16", with_dout=True)
+    check(sb, oracle, q, k, v, g)
+
+
 @pytest.mark.parametrize("d", [32, 64, 128])
 def test_bwd_finite_differences_T32(sb, oracle, gen, d):
     """Directional finite differences of the float64 forward at T = 32 against
