@@ -25,7 +25,8 @@ dK, dV = 2, its recomputation of the first two is not counted).  Nothing else
 rocprofv3 counter runs that cannot be made from inside this script; it is read
 from profiles/hbm_traffic_B8_H16_T4096_d128.txt (named in `traffic_source`) when
 that file is present.  It is a stored measurement of the kernel as it was when the
-profile was taken, not of this run.
+profile was taken, not of this run; the file records fingerprints of the kernel sources it
+was taken on, and `traffic_is_of_these_sources` says whether they are still the same.
 """
 from __future__ import annotations
 
@@ -82,17 +83,46 @@ def spread(ts):
     return {"ms_median": ts[len(ts) // 2], "ms_min": ts[0], "launches": len(ts)}
 
 
-def hbm_traffic(kernel):
-    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see the file)."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_B8_H16_T4096_d128.txt")
+TRAFFIC_FILE = os.path.join("profiles", "hbm_traffic_B8_H16_T4096_d128.txt")
+KERNEL_SOURCES = ("sb_fwd_bf16.hip", "sb_bwd_bf16.hip", "sb_decode.hip", "sb_mma.h")
+
+
+def source_fingerprint(name):
+    """sha256 of a kernel source with comments and white space removed: changes when the code does."""
+    import hashlib
+    import re
+    with open(os.path.join(ROOT, "paper_2410_17980_amd", "csrc", name)) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    text = re.sub(r"//[^\n]*", "", text)
+    return hashlib.sha256("".join(text.split()).encode()).hexdigest()[:16]
+
+
+def _traffic_record():
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, TRAFFIC_FILE)) as f:
             for line in f:
                 if line.startswith("JSON:"):
-                    return json.loads(line[5:]).get(kernel)
+                    return json.loads(line[5:])
     except OSError:
         pass
-    return None
+    return {}
+
+
+def hbm_traffic(kernel):
+    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see the file)."""
+    return _traffic_record().get(kernel)
+
+
+def hbm_traffic_is_current():
+    """True when the kernel sources are the ones the stored traffic figures were measured on."""
+    want = _traffic_record().get("kernel_sources")
+    if not want:
+        return None
+    try:
+        return all(source_fingerprint(n) == h for n, h in want.items())
+    except OSError:
+        return None
 
 
 def cpu_baseline(w, q, k, v, dout, n_heads, with_bwd):
@@ -480,7 +510,9 @@ def main():
     if with_bwd:
         out["bwd"]["frac_mfma_only_ceiling"] = tf_bwd / mfma_tf
     out["roofline"]["frac_mfma_only_ceiling"] = dom_tf / mfma_tf
-    out["roofline"]["traffic_source"] = "profiles/hbm_traffic_B8_H16_T4096_d128.txt (stored rocprofv3 run)"
+    out["roofline"]["traffic_source"] = TRAFFIC_FILE + " (stored rocprofv3 run)"
+    # false: the kernel sources changed since that run, the figure describes an older kernel
+    out["roofline"]["traffic_is_of_these_sources"] = hbm_traffic_is_current()
     out["fwd"]["frac_gemm_reference"] = tf_fwd / gemm_tf
     if not args.no_configs:
         out["configs"] = config_entries(sb, inputs, max(args.kernel_iters, 50),
